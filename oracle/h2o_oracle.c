@@ -1,0 +1,342 @@
+/*
+ * CPU oracle for the H2O (Heavy-Hitter Oracle) attention path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, fp64 statement of
+ * what the method computes.  It shares no code with the HIP library, is never
+ * linked into it and is never called by it; only the test-suite, the smoke
+ * check and the benchmark's cpu_baseline leg use it.
+ *
+ * One object models ONE head (one (batch, head) pair); heads are independent
+ * (the paper keeps/evicts per head and per layer, related-work comparison with
+ * cross-head accumulation).  The object is position-indexed: it remembers every
+ * token's key/value ever seen, a resident flag per position and one accumulated
+ * score per position.  There are no slots and nothing is ever compacted, so a
+ * reader can check each step against the paper by eye:
+ *
+ *   prefill  : exact / full-knowledge generative process (Sec. "Eviction
+ *              Policy", definition "generative process with full knowledge"):
+ *              o_i = softmax over K_{<=i}; accumulated scores are the column
+ *              sums of those rows (Algorithm 2, the accumulate line); then the
+ *              one-shot compression of App. A "System details/Pseudocode":
+ *              keep `recent` last tokens plus the `heavy` best-scoring older
+ *              ones, or everything if the prompt fits in the budget.
+ *   decode   : Definition 2.2 (generative process with eviction policy):
+ *              softmax restricted to the resident set (the "minus indicator"
+ *              term removes exp(0) of the zeroed rows), with the new token
+ *              attending to itself as in the exact process (o_{1,1} = 1);
+ *              Algorithm 2: accumulate, then evict
+ *              u = argmax_v F_score(G \ {v}), F_score = sum of accumulated
+ *              scores, i.e. the member with the smallest accumulated score,
+ *              restricted to tokens outside the recent window (Sec. 5.1
+ *              budget split, App. A).
+ *
+ * Readings taken where the paper is silent (all restated in the design notes):
+ *   - logits are scale * <q, k>; the paper's exp(QK^T) is scale = 1;
+ *   - after the step for position t the recent window is {t-R+1..t}
+ *     (it contains the new token); eviction candidates are resident
+ *     positions <= t-R; with R = 0 the new token is itself a candidate;
+ *   - ties: the smallest (score, position) pair is evicted;
+ *   - while fewer than `budget` tokens are stored nothing is evicted;
+ *   - `score_f32` != 0: accumulated scores are STORED in binary32 (the
+ *     precision the workload definitions give for scores): each step's
+ *     probability is rounded to binary32 and added in binary32; prefill column
+ *     sums are accumulated in fp64 and rounded once when stored.  With
+ *     `score_f32` == 0 everything stays fp64.  All other arithmetic is fp64.
+ *
+ * Pins (tests/test_oracle_pins.py): brute-force set-function evaluation on tiny
+ * inputs, reduction to textbook causal softmax attention when the budget
+ * covers the sequence, harmonic-number closed form for equal logits, sliding
+ * window for heavy = 0, mass conservation, set-size/window invariants.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct h2o_oracle {
+    int d;              /* head dimension */
+    int heavy;          /* H: heavy-hitter part of the budget */
+    int recent;         /* R: recent-window part of the budget */
+    int budget;         /* k = H + R */
+    double scale;       /* logit scale */
+    int score_f32;      /* store accumulated scores in binary32 */
+    int cap;            /* maximum number of tokens this object can see */
+    int t;              /* tokens seen so far == position of the next token */
+    int n_resident;
+    double *K;          /* [cap][d] every key ever seen */
+    double *V;          /* [cap][d] every value ever seen */
+    double *acc;        /* [cap] accumulated attention score per position */
+    unsigned char *resident; /* [cap] 1 if the token is in the cache */
+    double evicted_mass;     /* sum of acc[] over evicted tokens at eviction time */
+    double queries;          /* number of softmax rows accumulated so far */
+    double *s;          /* [cap] scratch: logits */
+    double *p;          /* [cap] scratch: probabilities */
+} h2o_oracle;
+
+h2o_oracle *h2o_oracle_new(int d, int heavy, int recent, double scale,
+                           int score_f32, int cap)
+{
+    if (d <= 0 || heavy < 0 || recent < 0 || heavy + recent < 1 || cap <= 0)
+        return NULL;
+    h2o_oracle *o = (h2o_oracle *)calloc(1, sizeof(*o));
+    if (!o) return NULL;
+    o->d = d; o->heavy = heavy; o->recent = recent; o->budget = heavy + recent;
+    o->scale = scale; o->score_f32 = score_f32; o->cap = cap;
+    o->K = (double *)calloc((size_t)cap * d, sizeof(double));
+    o->V = (double *)calloc((size_t)cap * d, sizeof(double));
+    o->acc = (double *)calloc(cap, sizeof(double));
+    o->resident = (unsigned char *)calloc(cap, 1);
+    o->s = (double *)calloc(cap, sizeof(double));
+    o->p = (double *)calloc(cap, sizeof(double));
+    if (!o->K || !o->V || !o->acc || !o->resident || !o->s || !o->p) {
+        free(o->K); free(o->V); free(o->acc); free(o->resident);
+        free(o->s); free(o->p); free(o);
+        return NULL;
+    }
+    return o;
+}
+
+void h2o_oracle_free(h2o_oracle *o)
+{
+    if (!o) return;
+    free(o->K); free(o->V); free(o->acc); free(o->resident);
+    free(o->s); free(o->p); free(o);
+}
+
+/* Add one probability to a stored score, in the storage precision. */
+static double add_score(const h2o_oracle *o, double stored, double prob)
+{
+    if (o->score_f32) {
+        volatile float a = (float)stored;
+        volatile float b = (float)prob;
+        volatile float r = a + b;
+        return (double)r;
+    }
+    return stored + prob;
+}
+
+static double dot(const double *a, const double *b, int d)
+{
+    double acc = 0.0;
+    for (int c = 0; c < d; ++c) acc += a[c] * b[c];
+    return acc;
+}
+
+/* Is (score a, position pa) strictly before (score b, position pb) in the
+ * eviction order: lower score first, equal scores -> lower position first. */
+static int evict_before(double a, int pa, double b, int pb)
+{
+    return (a < b) || (a == b && pa < pb);
+}
+
+/*
+ * One-shot compression of a prompt of n tokens whose scores are in acc[0..n):
+ * if the prompt fits in the budget keep everything; otherwise keep the last
+ * `recent` tokens and, among the older ones, evict the smallest
+ * (score, position) repeatedly until `heavy` of them remain (App. A:
+ * "K heavy hitters and K recent tokens", written as repeated single evictions
+ * so that it is the same rule the generation steps use).
+ */
+static void compress_prompt(h2o_oracle *o, int n)
+{
+    for (int j = 0; j < n; ++j) o->resident[j] = 1;
+    o->n_resident = n;
+    o->t = n;
+    if (n <= o->budget) return;
+    const int first_recent = n - o->recent;   /* window = [n-R, n) */
+    int older = first_recent;                 /* resident tokens outside it */
+    while (older > o->heavy) {
+        int u = -1;
+        for (int j = 0; j < first_recent; ++j) {
+            if (!o->resident[j]) continue;
+            if (u < 0 || evict_before(o->acc[j], j, o->acc[u], u)) u = j;
+        }
+        o->resident[u] = 0;
+        o->evicted_mass += o->acc[u];
+        --older; --o->n_resident;
+    }
+}
+
+/*
+ * Prompt phase.  Q, K, V are [n][d] row-major fp64.
+ *   colsum_out (nullable, [n]): full column sums of the causal softmax matrix
+ *       in fp64, before any rounding and before compression.
+ *   attn_out   (nullable, [n][d]): row i = sum_j p_ij V_j (full attention).
+ * Returns 0, or -1 on bad arguments / state (object must be empty).
+ */
+int h2o_oracle_prefill(h2o_oracle *o, const double *Q, const double *K,
+                       const double *V, int n, double *colsum_out,
+                       double *attn_out)
+{
+    if (!o || !Q || !K || !V || n <= 0 || n > o->cap || o->t != 0) return -1;
+    const int d = o->d;
+    memcpy(o->K, K, (size_t)n * d * sizeof(double));
+    memcpy(o->V, V, (size_t)n * d * sizeof(double));
+    for (int j = 0; j < n; ++j) o->acc[j] = 0.0;
+
+    /* Full-knowledge process: row i attends to keys 0..i (itself included). */
+    for (int i = 0; i < n; ++i) {
+        const double *qi = Q + (size_t)i * d;
+        double m = -INFINITY;
+        for (int j = 0; j <= i; ++j) {
+            o->s[j] = o->scale * dot(qi, K + (size_t)j * d, d);
+            if (o->s[j] > m) m = o->s[j];
+        }
+        double D = 0.0;
+        for (int j = 0; j <= i; ++j) { o->p[j] = exp(o->s[j] - m); D += o->p[j]; }
+        for (int j = 0; j <= i; ++j) {
+            o->p[j] /= D;
+            o->acc[j] += o->p[j];               /* column sum, fp64 */
+        }
+        if (attn_out) {
+            double *oi = attn_out + (size_t)i * d;
+            for (int c = 0; c < d; ++c) oi[c] = 0.0;
+            for (int j = 0; j <= i; ++j) {
+                const double *vj = V + (size_t)j * d;
+                for (int c = 0; c < d; ++c) oi[c] += o->p[j] * vj[c];
+            }
+        }
+    }
+    o->queries = (double)n;
+    if (colsum_out) memcpy(colsum_out, o->acc, (size_t)n * sizeof(double));
+    if (o->score_f32)
+        for (int j = 0; j < n; ++j) o->acc[j] = (double)(float)o->acc[j];
+
+    compress_prompt(o, n);
+    return 0;
+}
+
+/*
+ * Same compression as the tail of h2o_oracle_prefill, but with externally
+ * supplied scores: loads n tokens (K, V, score[j]) into an empty object and
+ * keeps the recent window plus the `heavy` best older tokens.  `queries` is
+ * the number of softmax rows the scores stand for (n after a prompt).
+ */
+int h2o_oracle_load_and_select(h2o_oracle *o, const double *K, const double *V,
+                               const double *score, int n)
+{
+    if (!o || !K || !V || !score || n <= 0 || n > o->cap || o->t != 0) return -1;
+    const int d = o->d;
+    memcpy(o->K, K, (size_t)n * d * sizeof(double));
+    memcpy(o->V, V, (size_t)n * d * sizeof(double));
+    for (int j = 0; j < n; ++j) {
+        o->acc[j] = o->score_f32 ? (double)(float)score[j] : score[j];
+    }
+    o->queries = (double)n;
+    compress_prompt(o, n);
+    return 0;
+}
+
+/*
+ * One generation step for the token at position t = tokens seen so far.
+ *   q, k_new, v_new : [d] fp64
+ *   out             : [d] attention output for this token
+ *   info[0] = evicted position (-1: nothing evicted)
+ *   info[1] = number of eviction candidates
+ *   low[0]  = lowest candidate score, low[1] = second lowest (+inf if none)
+ *   p_self_out (nullable) = probability the token gave itself
+ * Returns 0, or -1 on bad arguments / capacity exhausted.
+ */
+int h2o_oracle_decode(h2o_oracle *o, const double *q, const double *k_new,
+                      const double *v_new, double *out, int *info, double *low,
+                      double *p_self_out)
+{
+    if (!o || !q || !k_new || !v_new || !out || o->t >= o->cap) return -1;
+    const int d = o->d, t = o->t;
+    memcpy(o->K + (size_t)t * d, k_new, (size_t)d * sizeof(double));
+    memcpy(o->V + (size_t)t * d, v_new, (size_t)d * sizeof(double));
+    o->acc[t] = 0.0;
+    o->resident[t] = 1;                 /* G = S_{t-1} U {t} */
+    ++o->n_resident;
+
+    /* softmax over G only */
+    double m = -INFINITY;
+    for (int j = 0; j <= t; ++j) {
+        if (!o->resident[j]) continue;
+        o->s[j] = o->scale * dot(q, o->K + (size_t)j * d, d);
+        if (o->s[j] > m) m = o->s[j];
+    }
+    double D = 0.0;
+    for (int j = 0; j <= t; ++j)
+        if (o->resident[j]) { o->p[j] = exp(o->s[j] - m); D += o->p[j]; }
+    for (int c = 0; c < d; ++c) out[c] = 0.0;
+    for (int j = 0; j <= t; ++j) {
+        if (!o->resident[j]) continue;
+        o->p[j] /= D;
+        const double *vj = o->V + (size_t)j * d;
+        for (int c = 0; c < d; ++c) out[c] += o->p[j] * vj[c];
+        o->acc[j] = add_score(o, o->acc[j], o->p[j]);   /* accumulate */
+    }
+    o->queries += 1.0;
+    if (p_self_out) *p_self_out = o->p[t];
+
+    int evicted = -1, n_cand = 0;
+    double lowest = INFINITY, second = INFINITY;
+    if (o->n_resident > o->budget) {
+        /* candidates: resident positions outside the window {t-R+1..t} */
+        const int last_cand = t - o->recent;
+        for (int j = 0; j <= last_cand; ++j) {
+            if (!o->resident[j]) continue;
+            ++n_cand;
+            if (evicted < 0 || evict_before(o->acc[j], j, o->acc[evicted], evicted)) {
+                second = lowest; lowest = o->acc[j]; evicted = j;
+            } else if (o->acc[j] < second) {
+                second = o->acc[j];
+            }
+        }
+        if (evicted >= 0) {
+            o->resident[evicted] = 0;
+            o->evicted_mass += o->acc[evicted];
+            --o->n_resident;
+        }
+    }
+    if (info) { info[0] = evicted; info[1] = n_cand; }
+    if (low) { low[0] = lowest; low[1] = second; }
+    o->t = t + 1;
+    return 0;
+}
+
+/* Undo the eviction of `restore_pos` and evict `evict_pos` instead (used only
+ * when a checked implementation legitimately broke a near-tie the other way). */
+int h2o_oracle_resync(h2o_oracle *o, int restore_pos, int evict_pos)
+{
+    if (!o || restore_pos < 0 || restore_pos >= o->t || evict_pos < 0 ||
+        evict_pos >= o->t) return -1;
+    if (o->resident[restore_pos] || !o->resident[evict_pos]) return -1;
+    o->resident[restore_pos] = 1; o->evicted_mass -= o->acc[restore_pos];
+    o->resident[evict_pos] = 0;   o->evicted_mass += o->acc[evict_pos];
+    return 0;
+}
+
+/* ---- read-only accessors ---- */
+int h2o_oracle_tokens_seen(const h2o_oracle *o) { return o->t; }
+int h2o_oracle_num_resident(const h2o_oracle *o) { return o->n_resident; }
+double h2o_oracle_evicted_mass(const h2o_oracle *o) { return o->evicted_mass; }
+double h2o_oracle_queries(const h2o_oracle *o) { return o->queries; }
+int h2o_oracle_is_resident(const h2o_oracle *o, int pos)
+{ return (pos >= 0 && pos < o->t) ? o->resident[pos] : 0; }
+double h2o_oracle_score(const h2o_oracle *o, int pos)
+{ return (pos >= 0 && pos < o->t) ? o->acc[pos] : NAN; }
+
+/* Resident positions in ascending order with their scores; returns the count.
+ * pos_out/score_out must hold at least `budget` (or t, if smaller) entries. */
+int h2o_oracle_resident(const h2o_oracle *o, int *pos_out, double *score_out)
+{
+    int c = 0;
+    for (int j = 0; j < o->t; ++j) {
+        if (!o->resident[j]) continue;
+        if (pos_out) pos_out[c] = j;
+        if (score_out) score_out[c] = o->acc[j];
+        ++c;
+    }
+    return c;
+}
+
+/* Key/value history row (what a cache slot holding `pos` must contain). */
+int h2o_oracle_token_kv(const h2o_oracle *o, int pos, double *k_out, double *v_out)
+{
+    if (pos < 0 || pos >= o->t) return -1;
+    if (k_out) memcpy(k_out, o->K + (size_t)pos * o->d, (size_t)o->d * sizeof(double));
+    if (v_out) memcpy(v_out, o->V + (size_t)pos * o->d, (size_t)o->d * sizeof(double));
+    return 0;
+}

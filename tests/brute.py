@@ -1,0 +1,83 @@
+"""Brute-force re-derivation of the H2O process on tiny inputs (NumPy).
+
+Written independently of ``oracle/``: it works on the whole token sequence at
+once with dense boolean membership masks, takes the eviction decision by
+literally evaluating the set function F_score(G \\ {v}) for every allowed v and
+choosing the arg-max (Definition 4.3 / Algorithm 1, the argmax line), computes
+prompt column sums with an explicit double loop, and selects the prompt's heavy
+hitters by sorting instead of by repeated eviction.  It is only usable for a
+few dozen tokens.
+"""
+import math
+
+import numpy as np
+
+
+def _store(x, dtype):
+    return np.asarray(x, dtype=dtype).astype(np.float64)
+
+
+def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64):
+    """Q, K, V: [N, d] for all N = n + T tokens.  Returns a dict with
+    per-decode-step outputs, resident sets after every call, evicted tokens,
+    prompt column sums and final scores."""
+    Q = np.asarray(Q, np.float64); K = np.asarray(K, np.float64); V = np.asarray(V, np.float64)
+    N, d = Q.shape
+    k = heavy + recent
+    S = scale * (Q @ K.T)                       # every logit there is
+
+    acc = np.zeros(N)
+    member = np.zeros(N, dtype=bool)
+    sets, outs, evicted = [], [], []
+    colsum = np.zeros(n)
+    attn_prompt = np.zeros((n, d))
+    if n > 0:
+        P = np.zeros((n, n))
+        for i in range(n):
+            row = S[i, : i + 1]
+            e = np.exp(row - row.max())
+            P[i, : i + 1] = e / e.sum()
+        for j in range(n):                       # column sums, double loop
+            c = 0.0
+            for i in range(j, n):
+                c += P[i, j]
+            colsum[j] = c
+        attn_prompt = P @ V[:n]
+        acc[:n] = _store(colsum, score_dtype)
+        if n <= k:
+            member[:n] = True
+        else:
+            member[n - recent:n] = True
+            older = list(range(n - recent))
+            # best first: higher score, then higher position (so that what is
+            # dropped is the lowest score and, among equals, the lowest position)
+            older.sort(key=lambda j: (acc[j], j), reverse=True)
+            member[older[:heavy]] = True
+        sets.append(set(np.flatnonzero(member).tolist()))
+
+    for t in range(n, N):
+        G = member.copy()
+        G[t] = True
+        row = np.where(G, S[t], -np.inf)
+        e = np.exp(row - row.max())
+        p = e / e.sum()                           # zero outside G
+        outs.append(p @ V)
+        if score_dtype == np.float32:
+            acc = (acc.astype(np.float32) + p.astype(np.float32)).astype(np.float64)
+        else:
+            acc = acc + p
+        u = -1
+        if G.sum() > k:
+            members = np.flatnonzero(G).tolist()
+            allowed = [v for v in members if v <= t - recent]
+            best_f = None
+            for v in allowed:                     # ascending position
+                f = math.fsum(acc[s] for s in members if s != v)
+                if best_f is None or f > best_f:
+                    best_f, u = f, v
+            G[u] = False
+        evicted.append(u)
+        member = G
+        sets.append(set(np.flatnonzero(member).tolist()))
+    return dict(outs=np.array(outs), sets=sets, evicted=evicted, colsum=colsum,
+                attn_prompt=attn_prompt, acc=acc)

@@ -1,0 +1,334 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix.
+
+Each test checks ``oracle/`` against something that is NOT the oracle: a brute
+force written differently (tests/brute.py), a library routine the method must
+reduce to (torch.softmax causal attention), a closed form (harmonic numbers), or
+an invariant of the eviction policy (Definition 2.1, Definition 2.2).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.h2o_oracle import OracleHead
+from tests.brute import brute_h2o
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def make_inputs(seed, N, d, sigma=0.75):
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((N, d))
+    K = rng.standard_normal((N, d)) * np.exp(sigma * rng.standard_normal((N, 1)))
+    V = rng.standard_normal((N, d))
+    return Q, K, V
+
+
+def run_oracle(Q, K, V, n, heavy, recent, scale, score_f32=False):
+    N, d = Q.shape
+    o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=N)
+    sets, outs, evicted, lows = [], [], [], []
+    colsum = attn = None
+    if n > 0:
+        colsum, attn = o.prefill(Q[:n], K[:n], V[:n], want_attn=True)
+        sets.append(set(o.resident()[0].tolist()))
+    for t in range(n, N):
+        r = o.decode(Q[t], K[t], V[t])
+        outs.append(r.out); evicted.append(r.evicted); lows.append((r.lowest, r.second))
+        sets.append(set(o.resident()[0].tolist()))
+    return o, dict(sets=sets, outs=np.array(outs), evicted=evicted, colsum=colsum,
+                   attn=attn, lows=lows)
+
+
+# ---------------------------------------------------------------- N1 brute force
+@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("n,T,heavy,recent", [
+    (8, 12, 2, 2), (10, 10, 3, 1), (6, 14, 1, 3), (0, 16, 2, 3), (12, 8, 4, 0),
+    (9, 9, 0, 3), (5, 12, 3, 3), (14, 6, 2, 4), (4, 4, 4, 4),
+])
+def test_matches_brute_force(seed, n, T, heavy, recent):
+    d = 4
+    Q, K, V = make_inputs(1000 + seed, n + T, d)
+    scale = 0.5
+    o, got = run_oracle(Q, K, V, n, heavy, recent, scale)
+    ref = brute_h2o(Q, K, V, n, heavy, recent, scale)
+    # the comparison is only meaningful away from ties
+    for lo, se in got["lows"]:
+        if np.isfinite(se):
+            assert se - lo > 1e-9
+    assert got["sets"] == ref["sets"]
+    assert got["evicted"] == ref["evicted"]
+    np.testing.assert_allclose(got["outs"], ref["outs"], rtol=1e-12, atol=1e-13)
+    if n > 0:
+        np.testing.assert_allclose(got["colsum"], ref["colsum"], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(got["attn"], ref["attn_prompt"], rtol=1e-12, atol=1e-13)
+    pos, sc = o.resident()
+    np.testing.assert_allclose(sc, ref["acc"][pos], rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_matches_brute_force_f32_scores(seed):
+    """Scores stored in binary32: each probability is rounded to binary32 and
+    added in binary32 (numpy float32 arithmetic is the independent reference)."""
+    n, T, heavy, recent, d = 9, 14, 2, 3, 4
+    Q, K, V = make_inputs(2000 + seed, n + T, d)
+    o, got = run_oracle(Q, K, V, n, heavy, recent, 0.5, score_f32=True)
+    ref = brute_h2o(Q, K, V, n, heavy, recent, 0.5, score_dtype=np.float32)
+    assert got["sets"] == ref["sets"]
+    pos, sc = o.resident()
+    assert np.array_equal(sc, ref["acc"][pos])            # bit-exact
+    assert np.array_equal(sc, sc.astype(np.float32).astype(np.float64))
+
+
+# -------------------------------------------- N2 budget >= length == full attention
+def torch_causal_attention(Q, K, V, scale):
+    Qt, Kt, Vt = (torch.from_numpy(np.ascontiguousarray(x)) for x in (Q, K, V))
+    S = scale * Qt @ Kt.T
+    N = S.shape[0]
+    S = S.masked_fill(torch.triu(torch.ones(N, N, dtype=torch.bool), diagonal=1), float("-inf"))
+    P = torch.softmax(S, dim=-1)
+    return (P @ Vt).numpy(), P.sum(0).numpy()
+
+
+@pytest.mark.parametrize("n,T,d", [(24, 16, 8), (1, 30, 16), (40, 0, 4), (0, 20, 8)])
+def test_budget_covers_sequence_is_full_causal_attention(n, T, d):
+    Q, K, V = make_inputs(7, n + T, d, sigma=1.0)
+    scale = 1.0 / np.sqrt(d)
+    heavy, recent = (n + T + 1) // 2, (n + T) // 2 + 1
+    o, got = run_oracle(Q, K, V, n, heavy, recent, scale)
+    ref_out, ref_col = torch_causal_attention(Q, K, V, scale)
+    if n:
+        np.testing.assert_allclose(got["attn"], ref_out[:n], rtol=1e-11, atol=1e-12)
+    if T:
+        np.testing.assert_allclose(got["outs"], ref_out[n:], rtol=1e-11, atol=1e-12)
+    pos, sc = o.resident()
+    assert pos.tolist() == list(range(n + T))
+    np.testing.assert_allclose(sc, ref_col, rtol=1e-11, atol=1e-13)
+    assert all(e == -1 for e in got["evicted"])
+
+
+def test_prompt_column_sums_are_softmax_column_sums():
+    n, d = 33, 8
+    Q, K, V = make_inputs(11, n, d, sigma=1.0)
+    scale = 1.0 / np.sqrt(d)
+    o = OracleHead(d, 4, 4, scale, cap=n)
+    col, attn = o.prefill(Q, K, V, want_attn=True)
+    ref_out, ref_col = torch_causal_attention(Q, K, V, scale)
+    np.testing.assert_allclose(col, ref_col, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(attn, ref_out, rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------- N3 decode-from-empty == prefill
+def test_decode_from_empty_equals_prefill():
+    n, d = 20, 8
+    Q, K, V = make_inputs(3, n, d)
+    scale = 0.3
+    a = OracleHead(d, 10, 10, scale, cap=n)
+    last = None
+    for t in range(n):
+        last = a.decode(Q[t], K[t], V[t])
+    b = OracleHead(d, 10, 10, scale, cap=n)
+    col, attn = b.prefill(Q, K, V, want_attn=True)
+    pa, sa = a.resident(); pb, sb = b.resident()
+    assert pa.tolist() == pb.tolist() == list(range(n))
+    np.testing.assert_allclose(sa, sb, rtol=1e-12)
+    np.testing.assert_allclose(last.out, attn[-1], rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------- N4 equal logits: harmonic numbers
+def test_equal_logits_closed_form():
+    n, T, d, heavy, recent = 40, 25, 4, 5, 7
+    rng = np.random.default_rng(0)
+    K = rng.standard_normal((n + T, d)); V = rng.standard_normal((n + T, d))
+    Q = np.zeros((n + T, d))
+    o = OracleHead(d, heavy, recent, 1.0, cap=n + T)
+    col, attn = o.prefill(Q[:n], K[:n], V[:n], want_attn=True)
+    # 1-based: c_j = sum_{i=j..n} 1/i = H_n - H_{j-1}
+    Hn = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, n + 1))])
+    np.testing.assert_allclose(col, Hn[n] - Hn[:n], rtol=1e-13)
+    # row i of uniform attention is the running mean of V
+    np.testing.assert_allclose(attn, np.cumsum(V[:n], 0) / np.arange(1, n + 1)[:, None], rtol=1e-12,
+                               atol=1e-13)
+    expect_heavy = list(range(heavy))                # strictly decreasing scores
+    assert o.resident()[0].tolist() == expect_heavy + list(range(n - recent, n))
+    for t in range(n, n + T):
+        r = o.decode(Q[t], K[t], V[t])
+        # uniform over budget + 1 entries
+        assert abs(r.p_self - 1.0 / (heavy + recent + 1)) < 1e-15
+        # the token leaving the window has the lowest score and goes
+        assert r.evicted == t - recent
+        assert o.resident()[0].tolist() == expect_heavy + list(range(t - recent + 1, t + 1))
+        members = expect_heavy + list(range(t - recent, t + 1))
+        np.testing.assert_allclose(r.out, V[members].mean(0), rtol=1e-12, atol=1e-13)
+    # every heavy token gained 1/(k+1) per step
+    pos, sc = o.resident()
+    np.testing.assert_allclose(sc[:heavy], (Hn[n] - Hn[:heavy]) + T / (heavy + recent + 1.0),
+                               rtol=1e-12)
+
+
+# ------------------------------------------------------ N5 heavy = 0: sliding window
+def test_heavy_zero_is_sliding_window_attention():
+    n, T, d, recent = 10, 20, 8, 4
+    Q, K, V = make_inputs(5, n + T, d)
+    scale = 1.0 / np.sqrt(d)
+    o, got = run_oracle(Q, K, V, n, 0, recent, scale)
+    for idx, t in enumerate(range(n, n + T)):
+        lo = max(0, t - recent)                       # R cached tokens + the token itself
+        s = torch.from_numpy(scale * (K[lo:t + 1] @ Q[t]))
+        p = torch.softmax(s, 0).numpy()
+        np.testing.assert_allclose(got["outs"][idx], p @ V[lo:t + 1], rtol=1e-11, atol=1e-12)
+        assert got["sets"][idx + 1] == set(range(t - recent + 1, t + 1))
+        assert got["evicted"][idx] == t - recent
+
+
+def test_recent_zero_new_token_can_be_dropped():
+    """R = 0: the new token is itself a candidate (Algorithm 1's G_i includes i)."""
+    d = 4
+    o = OracleHead(d, 2, 0, 1.0, cap=8)
+    e = np.eye(d)
+    big = 6.0
+    # two prompt tokens that every later query loves
+    o.prefill(np.stack([e[0], e[0]]) * big, np.stack([e[0], e[0]]) * big, np.ones((2, d)))
+    r = o.decode(e[0] * big, -e[0] * big, np.ones(d))      # its own key repels its query
+    assert r.evicted == 2 and o.resident()[0].tolist() == [0, 1]
+    assert r.n_candidates == 3
+
+
+# ----------------------------------------------- N6-N8 invariants on random runs
+@pytest.mark.parametrize("seed", range(5))
+@pytest.mark.parametrize("n,T,heavy,recent,f32", [
+    (64, 64, 8, 8, False), (30, 100, 5, 11, True), (0, 80, 7, 3, False), (100, 30, 16, 16, True),
+])
+def test_invariants(seed, n, T, heavy, recent, f32):
+    d = 8
+    k = heavy + recent
+    Q, K, V = make_inputs(300 + seed, n + T, d, sigma=1.0)
+    o = OracleHead(d, heavy, recent, 1.0 / np.sqrt(d), score_f32=f32, cap=n + T)
+    if n:
+        o.prefill(Q[:n], K[:n], V[:n])
+    prev = set(o.resident()[0].tolist())
+    gone = set(range(n)) - prev
+    tol = 1e-4 if f32 else 1e-10
+    for t in range(n, n + T):
+        r = o.decode(Q[t], K[t], V[t])
+        pos, sc = o.resident()
+        cur = set(pos.tolist())
+        seen = t + 1
+        assert len(cur) == min(seen, k)                              # |S_i| = k (<= k while filling)
+        assert len(cur - prev) <= 1 and cur - prev <= {t}            # at most one token enters
+        assert len(prev - cur) <= 1                                  # at most one leaves
+        assert not (cur & gone)                                      # evicted tokens never return
+        gone |= (prev | {t}) - cur
+        assert set(range(max(0, seen - recent), seen)) <= cur        # recent window resident
+        assert abs(sc.sum() + o.evicted_mass - o.queries) < tol * seen   # mass conservation
+        assert o.queries == seen
+        # a score never exceeds the number of queries issued since the token arrived
+        assert np.all(sc <= (seen - pos) * (1 + 1e-6))
+        assert sc.sum() <= seen * (1 + 1e-6)
+        if r.evicted >= 0:
+            assert r.evicted <= t - recent and r.lowest <= r.second
+        prev = cur
+
+
+# ------------------------------------------------------------ N9 a dominant key
+def test_dominant_key_is_never_evicted():
+    n, T, d, heavy, recent = 20, 40, 8, 2, 3
+    rng = np.random.default_rng(9)
+    Q = rng.standard_normal((n + T, d)); Q[:, 0] = 3.0      # all queries agree on axis 0
+    K = rng.standard_normal((n + T, d)) * 0.1
+    V = rng.standard_normal((n + T, d))
+    star = 5
+    K[star] = 0.0; K[star, 0] = 20.0                         # logit ~ 60 above the rest
+    o = OracleHead(d, heavy, recent, 1.0, cap=n + T)
+    o.prefill(Q[:n], K[:n], V[:n])
+    for t in range(n, n + T):
+        r = o.decode(Q[t], K[t], V[t])
+        assert o.is_resident(star)
+        np.testing.assert_allclose(r.out, V[star], atol=1e-12)
+    # it collected (almost) one unit from every query issued after it arrived
+    assert abs(o.score(star) - (n + T - star)) < 1e-9
+
+
+# ----------------------------------------------------- N10 shift invariance, range
+def test_large_logits_do_not_overflow_and_shift_invariance():
+    n, T, d = 12, 12, 4
+    Q, K, V = make_inputs(21, n + T, d)
+    Q2 = Q * 40.0                                            # logits of order +-150
+    _, a = run_oracle(Q2, K, V, n, 3, 3, 1.0)
+    assert np.all(np.isfinite(a["outs"])) and np.all(np.isfinite(a["colsum"]))
+    # adding a constant vector c to every key shifts each row's logits by q.c:
+    # probabilities (hence everything) are unchanged
+    c = np.array([0.7, -1.1, 0.3, 2.0])
+    _, b = run_oracle(Q, K, V, n, 3, 3, 0.5)
+    _, s = run_oracle(Q, K + c, V, n, 3, 3, 0.5)
+    assert b["sets"] == s["sets"]
+    np.testing.assert_allclose(b["outs"], s["outs"], rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(b["colsum"], s["colsum"], rtol=1e-9)
+
+
+# ------------------------------------------------------------------ tie-breaking
+def test_exact_ties_evict_lowest_position():
+    d = 2
+    o = OracleHead(d, 3, 1, 1.0, cap=16)
+    K = np.zeros((4, d)); Q = np.zeros((4, d)); V = np.arange(8.0).reshape(4, d)
+    # decode four tokens with identical logits: scores 1+1/2+1/3+1/4, 1/2+1/3+1/4, ...
+    for t in range(4):
+        o.decode(Q[t], K[t], V[t])
+    # craft a tie: tokens 4 and 5 arrive with equal keys and get equal probability after
+    r = o.decode(np.zeros(d), np.zeros(d), np.zeros(d))     # t=4: full (k=4) -> someone leaves
+    assert r.evicted == 3                                    # lowest score among positions <= 3
+    # load exactly equal scores and check the position rule directly
+    o2 = OracleHead(d, 2, 1, 1.0, cap=8)
+    o2.load_and_select(np.zeros((5, d)), np.zeros((5, d)), np.array([0.5, 0.25, 0.25, 0.25, 9.0]))
+    assert o2.resident()[0].tolist() == [0, 3, 4]            # ties: lowest positions dropped first
+    r = o2.decode(np.zeros(d), np.zeros(d), np.zeros(d))     # all gain 1/4; candidates 0,3,4
+    assert r.evicted == 3 and r.lowest == 0.5 and r.second == 0.75
+
+
+def test_select_equals_repeated_eviction_and_respects_window():
+    rng = np.random.default_rng(4)
+    n, d, heavy, recent = 50, 4, 6, 9
+    K = rng.standard_normal((n, d)); V = rng.standard_normal((n, d))
+    score = rng.random(n); score[[3, 17, 30]] = 0.5          # a three-way tie in the middle
+    o = OracleHead(d, heavy, recent, 1.0, cap=n)
+    o.load_and_select(K, V, score)
+    older = sorted(range(n - recent), key=lambda j: (score[j], j), reverse=True)[:heavy]
+    assert o.resident()[0].tolist() == sorted(older) + list(range(n - recent, n))
+    assert abs(o.evicted_mass + o.resident()[1].sum() - score.sum()) < 1e-12
+
+
+# ----------------------------------------------------- resync (test bookkeeping)
+def test_resync_swaps_membership_and_mass():
+    Q, K, V = make_inputs(8, 30, 4)
+    o = OracleHead(4, 3, 3, 0.5, cap=30)
+    o.prefill(Q[:20], K[:20], V[:20])
+    r = o.decode(Q[20], K[20], V[20])
+    pos, sc = o.resident()
+    other = int(pos[0]) if pos[0] != r.evicted else int(pos[1])
+    total = sc.sum() + o.evicted_mass
+    o.resync(r.evicted, other)
+    pos2, sc2 = o.resident()
+    assert r.evicted in pos2 and other not in pos2 and len(pos2) == len(pos)
+    assert abs(sc2.sum() + o.evicted_mass - total) < 1e-12
+
+
+# ------------------------------------- the paper's one worked example (outcome only)
+def test_worked_example_outcome():
+    """Sec. 4.2, the illustration of Algorithm 1: budget 3, after the fourth
+    decoding step the third token is the one evicted.  The figure's numbers are
+    not in the text, so inputs realising the stated outcome are constructed."""
+    with open(os.path.join(GOLDEN, "alg1_worked_example.txt")) as f:
+        fields = dict(line.split("=", 1) for line in f.read().split() if "=" in line)
+    budget, step, victim = int(fields["budget"]), int(fields["step"]), int(fields["evicted_token"])
+    d = 4
+    e = np.eye(d)
+    # tokens 1, 2 and 4 have keys aligned with every query, token 3's key is opposed
+    K = np.stack([e[0], e[0], -e[0], e[0]]) * 2.0
+    Q = np.stack([e[0]] * 4) * 2.0
+    V = np.ones((4, d))
+    o = OracleHead(d, budget, 0, 1.0, cap=4)                 # Algorithm 1 has no recent window
+    ev = [o.decode(Q[t], K[t], V[t]).evicted for t in range(step)]
+    assert ev[:budget] == [-1] * budget                      # cache not full: expand only
+    assert ev[step - 1] == victim - 1                        # 1-based token 3
+    assert o.resident()[0].tolist() == [0, 1, 3]
