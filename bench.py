@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the H2O hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-graph]
+
+A "step" is one pass of the whole hot path over one batch of synthetic input of
+the OPT-6.7B-shaped layer workload: reset the cache, score the 2048-token prompt
+(row statistics + column sums on the matrix cores), compress it to the 410-slot
+budget, then 256 generation steps (fused attention + score accumulation +
+eviction + overwrite).  All inputs are resident in HBM before the clock starts.
+Prints one JSON line: tokens/s of the whole pass, the roofline record of the
+dominant kernel (the generation step, HBM-bound) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def decode_bytes_per_head_step(k: int, d: int, esize: int) -> int:
+    """Algorithmic bytes one head moves per generation step: K and V rows read
+    once, scores read + written and positions read (12 B per slot), q / k_new /
+    v_new read and the new K row, V row and output written (6 rows), plus the
+    victim's score and position written (8 B)."""
+    return 2 * k * d * esize + 12 * k + 6 * d * esize + 8
+
+
+def cpu_baseline(w, sample_heads: int):
+    """The oracle as it stands on this host's cores: prompt phase + all generation
+    steps for `sample_heads` heads of the workload, threads over heads."""
+    import torch
+    from oracle.h2o_oracle import OracleHead, map_heads
+    from paper_2306_14048_amd import synth
+    Q, K, V = synth.make_prompt(1, sample_heads, w.prompt, w.head_dim, w.dtype, w.sigma, "cpu")
+    qs, ks, vs = synth.make_steps(1, sample_heads, w.head_dim, w.steps, w.dtype, w.sigma, "cpu")
+    Q, K, V = Q.double().numpy(), K.double().numpy(), V.double().numpy()
+    qs, ks, vs = qs.double().numpy(), ks.double().numpy(), vs.double().numpy()
+    scale = 1.0 / float(w.head_dim) ** 0.5
+
+    def one(h):
+        o = OracleHead(w.head_dim, w.heavy, w.recent, scale, score_f32=True, cap=w.prompt + w.steps)
+        o.prefill(Q[0, h], K[0, h], V[0, h])
+        for s in range(w.steps):
+            o.decode(qs[s, 0, h], ks[s, 0, h], vs[s, 0, h])
+        return o.t
+
+    t0 = time.perf_counter()
+    _, threads = map_heads(one, range(sample_heads))
+    dt = time.perf_counter() - t0
+    heads = w.batch * w.heads
+    whole = dt * heads / sample_heads                    # heads are independent and identical
+    return {"value": w.batch * w.steps / whole, "unit": "tokens/s", "cores": threads,
+            "kind": "oracle",
+            "sample": "%d of %d heads, full prompt phase + %d steps each, %.1f s measured, "
+                      "scaled by head count" % (sample_heads, heads, w.steps, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="opt6.7b_layer_f16")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (heads are independent and would "
+                 "shard with no communication, but no multi-GPU path is part of it); use --gpus 1")
+
+    import torch
+    from paper_2306_14048_amd import binding as hb, synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    w = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    B, Hh, d, n, T = w.batch, w.heads, w.head_dim, w.prompt, w.steps
+    k = w.budget
+    esize = 4 if w.dtype == torch.float32 else 2
+
+    Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev)
+    qs, ks, vs = synth.make_steps(B, Hh, d, T, w.dtype, w.sigma, dev)
+    outs = torch.empty((T, B, Hh, d), dtype=w.dtype, device=dev)
+    cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
+    ws = cache.workspace(n)
+    step_stride = B * Hh * d * esize
+    qp, kp, vp, op = qs.data_ptr(), ks.data_ptr(), vs.data_ptr(), outs.data_ptr()
+    Qp, Kp, Vp, wsp, wsn = Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel()
+    h = cache.handle
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def one_pass(stream, timed_events=False):
+        sp = stream.cuda_stream
+        hb.h2o_cache_reset(h, sp)
+        if timed_events:
+            ev[0].record(stream)
+        hb.h2o_prefill_scores(h, Qp, Kp, Vp, n, wsp, wsn, None, sp)
+        if timed_events:
+            ev[1].record(stream)
+        for s in range(T):
+            off = s * step_stride
+            hb.h2o_decode_step(h, qp + off, kp + off, vp + off, op + off, sp)
+        if timed_events:
+            ev[2].record(stream)
+
+    stream = torch.cuda.Stream(device=dev)
+    torch.cuda.synchronize()
+    graph = None
+    with torch.cuda.stream(stream):
+        for _ in range(max(1, args.warmup)):
+            one_pass(stream)
+        stream.synchronize()
+        if not args.no_graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                one_pass(stream)
+            graph.replay()
+            stream.synchronize()
+
+        # kernel-level timing with events on the launch stream (eager launches:
+        # events cannot be placed inside a captured graph)
+        prefill_ms, decode_ms = [], []
+        for _ in range(3):
+            one_pass(stream, timed_events=True)
+            stream.synchronize()
+            prefill_ms.append(ev[0].elapsed_time(ev[1]))
+            decode_ms.append(ev[1].elapsed_time(ev[2]))
+
+        # whole-pass timing
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            if graph is not None:
+                graph.replay()
+            else:
+                one_pass(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+
+        # generation-only timing in the same launch mode (graph of T steps)
+        dec_graph_us = None
+        if graph is not None:
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2, stream=stream):
+                for s in range(T):
+                    off = s * step_stride
+                    hb.h2o_decode_step(h, qp + off, kp + off, vp + off, op + off, stream.cuda_stream)
+            g2.replay()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            e0.record(stream)
+            for _ in range(reps):
+                g2.replay()
+            e1.record(stream)
+            stream.synchronize()
+            dec_graph_us = e0.elapsed_time(e1) * 1e3 / (reps * T)
+
+    ms_per_step = dt * 1e3 / args.steps
+    tokens_per_s = B * T / (dt / args.steps)
+    dec_us_eager = min(decode_ms) * 1e3 / T
+    dec_us = dec_graph_us if dec_graph_us is not None else dec_us_eager
+    bytes_per_launch = decode_bytes_per_head_step(k, d, esize) * B * Hh
+    achieved = bytes_per_launch / (dec_us * 1e-6) / 1e9
+    rec = {
+        "metric": "H2O decode step: achieved HBM GB/s (% peak) + tokens/s, OPT-6.7B-shape layer",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": {torch.float16: "f16", torch.bfloat16: "bf16", torch.float32: "f32"}[w.dtype],
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "heads": Hh, "head_dim": d, "prompt": n,
+                   "decode_steps": T, "budget": k, "heavy": w.heavy, "recent": w.recent,
+                   "step": "cache reset + prompt scoring/compression + %d generation steps" % T,
+                   "launch": "eager" if graph is None else "hip-graph replay"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "decode_kernel", "bytes_per_launch": bytes_per_launch,
+                     "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager},
+        "decode_tokens_per_s": B / (dec_us * 1e-6),
+        "prefill_ms": min(prefill_ms),
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w, args.cpu_heads)
+    print(json.dumps(rec))
+    cache.close()
+
+
+if __name__ == "__main__":
+    main()

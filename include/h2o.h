@@ -1,0 +1,188 @@
+/*
+ * h2o.h — C ABI of the MI355X (gfx950) H2O attention hot path.
+ *
+ * H2O ("Heavy-Hitter Oracle", arXiv 2306.14048) keeps a KV cache of fixed size
+ * k = heavy + recent per attention head.  At every generation step the new
+ * token attends to the k cached tokens and to itself (Definition 2.2: softmax
+ * restricted to the tokens in the cache), the step's probabilities are added to
+ * one accumulated score per cached token (Algorithm 2, accumulate line), and
+ * the cached token with the smallest accumulated score outside the `recent`
+ * most recent ones is evicted (Definition 4.3 with F_score = sum of accumulated
+ * scores; budget split of Sec. 5.1 / App. A) and its storage is overwritten in
+ * place by the new token's key/value (Sec. 4.2 "Implementation details": no
+ * swap, fill directly).  The prompt phase seeds the scores with the column sums
+ * of the prompt's causal softmax matrix and keeps `heavy` best + `recent` last
+ * tokens (App. A, pseudocode commentary).  Heads are independent.
+ *
+ * Conventions
+ *   - every pointer named dev/Q/K/V/q/k_new/v_new/out/colsum/acc/pos/workspace
+ *     is a DEVICE pointer owned by the caller; the library never allocates or
+ *     frees device memory and never synchronises: all work is enqueued on the
+ *     `hip_stream` argument (a hipStream_t passed as void*, NULL = default
+ *     stream) and the call returns at once;
+ *   - the only thing the library owns is the small host-side handle
+ *     `h2o_cache`, created by h2o_cache_init and released by h2o_cache_destroy;
+ *   - device pointers must be 16-byte aligned;
+ *   - layouts are contiguous, last index fastest:
+ *       prompt  Q, K, V        [batch, heads, n, head_dim]     (cfg.dtype)
+ *       step    q, k_new, v_new, out  [batch, heads, head_dim] (cfg.dtype)
+ *       cache   K, V           [batch, heads, k, head_dim]     (cfg.dtype)
+ *               acc            [batch, heads, k]  float  accumulated scores
+ *               pos            [batch, heads, k]  int32  token position held
+ *                                                  by the slot, -1 = free
+ *     Which slot holds which token is an implementation detail: only the set
+ *     of positions is meaningful.
+ *   - positions count tokens from 0; `t` = number of tokens seen so far is the
+ *     same for all heads (prompts are padded to one length, Sec. 5.3) and is
+ *     tracked on the host handle;
+ *   - every function returns an h2o_status (0 = success, negative = error);
+ *     on error nothing has been enqueued unless stated otherwise.
+ */
+#ifndef H2O_H
+#define H2O_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum h2o_status {
+    H2O_OK = 0,
+    H2O_EINVAL = -1,        /* null pointer, non-positive size, misaligned pointer */
+    H2O_EUNSUPPORTED = -2,  /* head_dim not in {64, 128}, budget or prompt too large */
+    H2O_ENOMEM = -3,        /* caller-provided buffer too small */
+    H2O_ESTATE = -4,        /* call not legal in the cache's current state */
+    H2O_EHIP = -5           /* the HIP runtime reported an error */
+} h2o_status;
+
+typedef enum h2o_dtype { H2O_F32 = 0, H2O_F16 = 1, H2O_BF16 = 2 } h2o_dtype;
+
+/* Largest supported budget (heavy + recent) and prompt length. */
+#define H2O_MAX_BUDGET 4096
+#define H2O_MAX_PROMPT 65536
+
+typedef struct h2o_config {
+    int32_t batch;      /* B  >= 1 */
+    int32_t heads;      /* Hh >= 1 */
+    int32_t head_dim;   /* d: 64 or 128 */
+    int32_t heavy;      /* H >= 0, heavy-hitter share of the budget */
+    int32_t recent;     /* R >= 0, recent-window share; H + R >= 1 */
+    int32_t dtype;      /* h2o_dtype of Q/K/V/q/k/v/out and of the cached K/V */
+    float scale;        /* logit scale; 0 selects 1/sqrt(head_dim) */
+} h2o_config;
+
+typedef struct h2o_cache h2o_cache;   /* opaque host-side handle */
+
+/* Device bytes needed for one cache: K | V | acc | pos, each 256-byte aligned.
+ * Returns 0 for an invalid configuration. */
+size_t h2o_cache_bytes(const h2o_config *cfg);
+
+/* Device bytes of scratch the prompt phase needs for a prompt of n tokens
+ * (row log-sum-exps and column sums, float [batch, heads, n] each).
+ * Returns 0 for invalid arguments. */
+size_t h2o_prefill_workspace_bytes(const h2o_config *cfg, int32_t n);
+
+/*
+ * Creates a handle over caller-owned device memory `dev_mem` of `bytes` bytes
+ * (>= h2o_cache_bytes) and enqueues the fill that marks every slot free
+ * (pos = -1, acc = 0).  The cache starts empty with t = 0.
+ * Errors: EINVAL, EUNSUPPORTED, ENOMEM (bytes too small), EHIP.
+ */
+int h2o_cache_init(const h2o_config *cfg, void *dev_mem, size_t bytes,
+                   void *hip_stream, h2o_cache **out);
+
+/* Marks every slot free again and sets t = 0 (enqueued on the stream). */
+int h2o_cache_reset(h2o_cache *cache, void *hip_stream);
+
+/* Releases the host handle only (device memory stays the caller's). */
+void h2o_cache_destroy(h2o_cache *cache);
+
+/*
+ * Prompt scoring (exact generative process, App. D "Eviction policy"; scores as
+ * in Algorithm 2's accumulate line): for every head
+ *     S_ij = scale * <Q_i, K_j>  (j <= i),   P = row-softmax(S),
+ *     colsum_j = sum_{i >= j} P_ij.
+ * Two MFMA passes: row log-sum-exp, then exp(S - LSE) reduced over rows.
+ *   Q, K        [batch, heads, n, head_dim] in cfg->dtype
+ *   workspace   >= h2o_prefill_workspace_bytes(cfg, n)
+ *   colsum_out  float [batch, heads, n]
+ * Needs no cache.  Errors: EINVAL, EUNSUPPORTED (n > H2O_MAX_PROMPT), ENOMEM, EHIP.
+ */
+int h2o_prefill_colsum(const h2o_config *cfg, const void *Q, const void *K,
+                       int32_t n, void *workspace, size_t ws_bytes,
+                       float *colsum_out, void *hip_stream);
+
+/*
+ * Prompt compression (App. A: "K heavy hitters and K recent tokens ...
+ * otherwise return all"): given a score per prompt token, keep the last
+ * `recent` tokens and the `heavy` highest-scoring older ones (all n tokens if
+ * n <= heavy + recent; equal scores: the higher position is kept), copy their
+ * K/V rows into slots in ascending position order, set acc/pos, mark the rest
+ * free, and set t = n.  The cache must be empty (fresh or reset).
+ *   K, V    [batch, heads, n, head_dim];   score  float [batch, heads, n]
+ * Errors: EINVAL, EUNSUPPORTED, ESTATE (cache not empty), EHIP.
+ */
+int h2o_prefill_select(h2o_cache *cache, const void *K, const void *V,
+                       const float *score, int32_t n, void *hip_stream);
+
+/*
+ * The whole prompt phase: h2o_prefill_colsum followed by h2o_prefill_select on
+ * the sums.  `colsum_out` (nullable) additionally receives the column sums.
+ * Q is only used for scoring; V only for the copy into the cache.
+ */
+int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K,
+                       const void *V, int32_t n, void *workspace,
+                       size_t ws_bytes, float *colsum_out, void *hip_stream);
+
+/*
+ * One generation step for the token at position t, one fused kernel launch
+ * (Definition 2.2, Algorithm 2, App. A decode commentary), per head:
+ *   1. logits  s_j = scale * <q, K[slot j]> for every occupied slot, and
+ *      s_self = scale * <q, k_new>;
+ *   2. p = softmax over the occupied slots and the token itself;
+ *   3. out = sum_j p_j V[slot j] + p_self * v_new;
+ *   4. acc[j] += p_j (binary32 add of the binary32-rounded probability);
+ *   5. if a slot is free the new token takes the lowest-indexed free slot;
+ *      otherwise the occupied slot with the smallest (acc, pos) among those
+ *      with pos <= t - recent is evicted (with recent == 0 the new token,
+ *      scored p_self, competes and may itself be dropped);
+ *   6. the chosen slot gets K = k_new, V = v_new, acc = p_self, pos = t.
+ * Then t becomes t + 1.  The cache is read exactly once.
+ * Errors: EINVAL, EHIP.
+ */
+int h2o_decode_step(h2o_cache *cache, const void *q, const void *k_new,
+                    const void *v_new, void *out, void *hip_stream);
+
+/* Copies pos / acc (each [batch, heads, k], device pointers, either may be
+ * NULL) out of the cache, ordered after earlier work on the stream. */
+int h2o_cache_snapshot(const h2o_cache *cache, int32_t *pos_out, float *acc_out,
+                       void *hip_stream);
+
+/*
+ * Loads a complete cache state (checkpoint restore; also how tests start a
+ * generation from a state computed elsewhere): K, V [batch, heads, k, head_dim],
+ * acc, pos [batch, heads, k] are copied in and t is set to `tokens_seen`.
+ * Every pos must be -1 or in [0, tokens_seen) and unique within a head (not
+ * checked on the device).  Errors: EINVAL, EHIP.
+ */
+int h2o_cache_restore(h2o_cache *cache, const void *K, const void *V,
+                      const float *acc, const int32_t *pos,
+                      int32_t tokens_seen, void *hip_stream);
+
+/* Number of tokens seen so far (prompt length + steps), or H2O_EINVAL. */
+int h2o_cache_tokens_seen(const h2o_cache *cache);
+
+/* Device addresses of the cache's four regions inside the caller's memory
+ * (any output pointer may be NULL). */
+int h2o_cache_regions(const h2o_cache *cache, void **K, void **V, float **acc,
+                      int32_t **pos);
+
+/* Static description of a status code. */
+const char *h2o_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* H2O_H */

@@ -1,0 +1,265 @@
+"""ctypes binding of libh2o_hip.so: same entry points as include/h2o.h.
+
+Argument marshalling only (tensor -> device pointer, stream -> hipStream_t);
+every step of the path runs in the HIP kernels.  PyTorch is used for device
+memory and streams.  There is no fallback: if the library has not been built
+(`python -m paper_2306_14048_amd.build`) importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libh2o_hip.so")
+
+H2O_OK, H2O_EINVAL, H2O_EUNSUPPORTED, H2O_ENOMEM, H2O_ESTATE, H2O_EHIP = 0, -1, -2, -3, -4, -5
+H2O_F32, H2O_F16, H2O_BF16 = 0, 1, 2
+H2O_MAX_BUDGET = 4096
+H2O_MAX_PROMPT = 65536
+
+DTYPES = {torch.float32: H2O_F32, torch.float16: H2O_F16, torch.bfloat16: H2O_BF16}
+TORCH_DTYPES = {v: k for k, v in DTYPES.items()}
+
+EXPORTS = (
+    "h2o_cache_bytes", "h2o_prefill_workspace_bytes", "h2o_cache_init", "h2o_cache_reset",
+    "h2o_cache_destroy", "h2o_prefill_colsum", "h2o_prefill_select", "h2o_prefill_scores",
+    "h2o_decode_step", "h2o_cache_snapshot", "h2o_cache_restore", "h2o_cache_tokens_seen",
+    "h2o_cache_regions", "h2o_status_str",
+)
+
+
+class h2o_config(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("heavy", ctypes.c_int32), ("recent", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class H2OError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, h2o_status_str(status), status))
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libh2o_hip.so is not built; run `python -m paper_2306_14048_amd.build` "
+                      "(there is no CPU fallback)")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+_cfgp = ctypes.POINTER(h2o_config)
+_lib.h2o_cache_bytes.restype = _sz
+_lib.h2o_cache_bytes.argtypes = [_cfgp]
+_lib.h2o_prefill_workspace_bytes.restype = _sz
+_lib.h2o_prefill_workspace_bytes.argtypes = [_cfgp, _i32]
+_lib.h2o_cache_init.argtypes = [_cfgp, _vp, _sz, _vp, ctypes.POINTER(_vp)]
+_lib.h2o_cache_reset.argtypes = [_vp, _vp]
+_lib.h2o_cache_destroy.argtypes = [_vp]
+_lib.h2o_cache_destroy.restype = None
+_lib.h2o_prefill_colsum.argtypes = [_cfgp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
+_lib.h2o_prefill_select.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp]
+_lib.h2o_prefill_scores.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
+_lib.h2o_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
+_lib.h2o_cache_snapshot.argtypes = [_vp, _vp, _vp, _vp]
+_lib.h2o_cache_restore.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
+_lib.h2o_cache_tokens_seen.argtypes = [_vp]
+_lib.h2o_cache_regions.argtypes = [_vp] + [ctypes.POINTER(_vp)] * 4
+_lib.h2o_status_str.restype = ctypes.c_char_p
+_lib.h2o_status_str.argtypes = [ctypes.c_int]
+
+
+def _ptr(x):
+    """Device (or null) pointer of a tensor / raw int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != H2O_OK:
+        raise H2OError(rc, where)
+
+
+def make_config(batch, heads, head_dim, heavy, recent, dtype, scale=0.0) -> h2o_config:
+    if isinstance(dtype, torch.dtype):
+        dtype = DTYPES[dtype]
+    return h2o_config(int(batch), int(heads), int(head_dim), int(heavy), int(recent), int(dtype),
+                      float(scale))
+
+
+def h2o_status_str(status: int) -> str:
+    return _lib.h2o_status_str(int(status)).decode()
+
+
+def h2o_cache_bytes(cfg: h2o_config) -> int:
+    return int(_lib.h2o_cache_bytes(ctypes.byref(cfg)))
+
+
+def h2o_prefill_workspace_bytes(cfg: h2o_config, n: int) -> int:
+    return int(_lib.h2o_prefill_workspace_bytes(ctypes.byref(cfg), int(n)))
+
+
+def h2o_cache_init(cfg: h2o_config, dev_mem, nbytes: int, stream=None) -> int:
+    """Returns the opaque handle (an integer address)."""
+    out = _vp()
+    _check(_lib.h2o_cache_init(ctypes.byref(cfg), _ptr(dev_mem), int(nbytes), _stream(stream),
+                               ctypes.byref(out)), "h2o_cache_init")
+    return out.value
+
+
+def h2o_cache_reset(cache: int, stream=None) -> None:
+    _check(_lib.h2o_cache_reset(cache, _stream(stream)), "h2o_cache_reset")
+
+
+def h2o_cache_destroy(cache: int) -> None:
+    _lib.h2o_cache_destroy(cache)
+
+
+def h2o_prefill_colsum(cfg, Q, K, n, workspace, ws_bytes, colsum_out, stream=None) -> None:
+    _check(_lib.h2o_prefill_colsum(ctypes.byref(cfg), _ptr(Q), _ptr(K), int(n), _ptr(workspace),
+                                   int(ws_bytes), _ptr(colsum_out), _stream(stream)),
+           "h2o_prefill_colsum")
+
+
+def h2o_prefill_select(cache, K, V, score, n, stream=None) -> None:
+    _check(_lib.h2o_prefill_select(cache, _ptr(K), _ptr(V), _ptr(score), int(n), _stream(stream)),
+           "h2o_prefill_select")
+
+
+def h2o_prefill_scores(cache, Q, K, V, n, workspace, ws_bytes, colsum_out=None, stream=None) -> None:
+    _check(_lib.h2o_prefill_scores(cache, _ptr(Q), _ptr(K), _ptr(V), int(n), _ptr(workspace),
+                                   int(ws_bytes), _ptr(colsum_out), _stream(stream)),
+           "h2o_prefill_scores")
+
+
+def h2o_decode_step(cache, q, k_new, v_new, out, stream=None) -> None:
+    _check(_lib.h2o_decode_step(cache, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                _stream(stream)), "h2o_decode_step")
+
+
+def h2o_cache_snapshot(cache, pos_out=None, acc_out=None, stream=None) -> None:
+    _check(_lib.h2o_cache_snapshot(cache, _ptr(pos_out), _ptr(acc_out), _stream(stream)),
+           "h2o_cache_snapshot")
+
+
+def h2o_cache_restore(cache, K, V, acc, pos, tokens_seen, stream=None) -> None:
+    _check(_lib.h2o_cache_restore(cache, _ptr(K), _ptr(V), _ptr(acc), _ptr(pos), int(tokens_seen),
+                                  _stream(stream)), "h2o_cache_restore")
+
+
+def h2o_cache_tokens_seen(cache) -> int:
+    return int(_lib.h2o_cache_tokens_seen(cache))
+
+
+def h2o_cache_regions(cache):
+    """Device addresses (K, V, acc, pos) of the cache's regions."""
+    K, V, A, P = _vp(), _vp(), _vp(), _vp()
+    _check(_lib.h2o_cache_regions(cache, ctypes.byref(K), ctypes.byref(V), ctypes.byref(A),
+                                  ctypes.byref(P)), "h2o_cache_regions")
+    return K.value, V.value, A.value, P.value
+
+
+class H2OCache:
+    """Owns the device memory (a torch byte tensor) and the library handle of
+    one cache; methods forward to the entry points of the same name."""
+
+    def __init__(self, batch, heads, head_dim, heavy, recent, dtype=torch.float16, scale=0.0,
+                 device="cuda", stream=None):
+        self.cfg = make_config(batch, heads, head_dim, heavy, recent, dtype, scale)
+        self.dtype = dtype if isinstance(dtype, torch.dtype) else TORCH_DTYPES[dtype]
+        self.device = torch.device(device)
+        self.budget = int(heavy) + int(recent)
+        nbytes = h2o_cache_bytes(self.cfg)
+        if nbytes == 0:
+            raise H2OError(H2O_EINVAL, "h2o_cache_bytes")
+        self.nbytes = nbytes
+        self.mem = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.handle = h2o_cache_init(self.cfg, self.mem, nbytes, stream)
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "handle", None):
+            h2o_cache_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    @property
+    def shape_heads(self):
+        return self.cfg.batch, self.cfg.heads
+
+    def workspace(self, n: int) -> torch.Tensor:
+        need = h2o_prefill_workspace_bytes(self.cfg, n)
+        if need == 0:
+            raise H2OError(H2O_EUNSUPPORTED, "h2o_prefill_workspace_bytes")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def reset(self, stream=None):
+        h2o_cache_reset(self.handle, stream)
+
+    def prefill_scores(self, Q, K, V, colsum_out=None, stream=None):
+        n = Q.shape[-2]
+        ws = self.workspace(n)
+        h2o_prefill_scores(self.handle, Q, K, V, n, ws, ws.numel(), colsum_out, stream)
+
+    def prefill_select(self, K, V, score, stream=None):
+        h2o_prefill_select(self.handle, K, V, score, K.shape[-2], stream)
+
+    def decode_step(self, q, k_new, v_new, out, stream=None):
+        h2o_decode_step(self.handle, q, k_new, v_new, out, stream)
+
+    def snapshot(self, stream=None):
+        B, Hh = self.shape_heads
+        pos = torch.empty((B, Hh, self.budget), dtype=torch.int32, device=self.device)
+        acc = torch.empty((B, Hh, self.budget), dtype=torch.float32, device=self.device)
+        h2o_cache_snapshot(self.handle, pos, acc, stream)
+        return pos, acc
+
+    def restore(self, K, V, acc, pos, tokens_seen, stream=None):
+        h2o_cache_restore(self.handle, K, V, acc, pos, tokens_seen, stream)
+
+    @property
+    def tokens_seen(self) -> int:
+        return h2o_cache_tokens_seen(self.handle)
+
+    def kv_views(self):
+        """Tensor views [B, Hh, k, d] of the cached keys and values (aliases of
+        the cache memory, for inspection)."""
+        B, Hh = self.shape_heads
+        d, k = self.cfg.head_dim, self.budget
+        kaddr, vaddr, _, _ = h2o_cache_regions(self.handle)
+        base = self.mem.data_ptr()
+        es = 4 if self.dtype == torch.float32 else 2
+        cnt = B * Hh * k * d
+
+        def view(addr):
+            off = addr - base
+            return self.mem[off:off + cnt * es].view(self.dtype).view(B, Hh, k, d)
+        return view(kaddr), view(vaddr)
+
+
+def prefill_colsum(cfg: h2o_config, Q, K, stream=None) -> torch.Tensor:
+    """Convenience wrapper: allocates workspace and output with torch and calls
+    h2o_prefill_colsum.  Q, K: [B, Hh, n, d]."""
+    n = Q.shape[-2]
+    need = h2o_prefill_workspace_bytes(cfg, n)
+    if need == 0:
+        raise H2OError(H2O_EUNSUPPORTED, "h2o_prefill_workspace_bytes")
+    ws = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    out = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
+    h2o_prefill_colsum(cfg, Q, K, n, ws, need, out, stream)
+    return out

@@ -1,0 +1,433 @@
+// Fused H2O generation step for gfx950: one workgroup per (batch, head).
+//
+// Per head the kernel reads the k cached key rows once (logits), does an exact
+// softmax over the occupied slots and the new token itself (Definition 2.2: the
+// normaliser only counts tokens that are in the cache; the token attends to
+// itself as in the exact process), reads the k cached value rows once (output),
+// adds the probabilities to the per-slot accumulated scores (Algorithm 2,
+// accumulate line), picks the slot to give up (Definition 4.3 with the sum of
+// accumulated scores as F_score: the smallest score outside the recent window)
+// and overwrites it in place with the new token (Sec. 4.2 implementation
+// details: no swap, fill directly).
+//
+// Memory plan.  A cache row (head_dim elements) is read by LPR = row_bytes/16
+// neighbouring lanes with one 128-bit load each, so a wave covers 64/LPR whole
+// rows = 1 KiB of contiguous memory per load instruction and the workgroup
+// covers RPI rows per "round".  The key rounds followed by the value rounds
+// form one stream that is pulled through a ring of U register buffers per
+// wave: a buffer is refilled with the entry U places ahead as soon as it has
+// been consumed, so value rows are already in flight while the workgroup sits
+// in the softmax barriers and HBM never idles.  Logits, probabilities and the
+// per-slot bookkeeping live in LDS.
+//
+// Arithmetic.  q.k products are accumulated in fp64 (inputs widened exactly),
+// reduced over the row's lanes with DPP moves, and the softmax is evaluated in
+// fp64; each probability is rounded once to binary32 and added to the binary32
+// score.  That makes the stored scores, and with them the eviction decisions,
+// reproducible against an fp64 reference; the kernel is HBM-bound and the extra
+// ALU work hides behind the stream.  P.V is accumulated in fp32.
+#include "h2o_internal.h"
+
+namespace {
+
+// Workgroup barrier that waits for this wave's LDS traffic only, so global
+// loads issued earlier (prefetched rows) stay in flight across it.
+__device__ inline void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// ---- DPP helpers (row = 16 lanes) ---------------------------------------------
+constexpr int DPP_XOR1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141; // lane i <-> 7-i inside each 8 lanes
+constexpr int DPP_MIRROR = 0x140;      // lane i <-> 15-i inside each 16 lanes
+
+template <int CTRL> __device__ inline int dpp(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL> __device__ inline double dpp(double v)
+{
+    return __hiloint2double(dpp<CTRL>(__double2hiint(v)), dpp<CTRL>(__double2loint(v)));
+}
+template <int CTRL> __device__ inline unsigned long long dpp(unsigned long long v)
+{
+    const unsigned hi = (unsigned)dpp<CTRL>((int)(v >> 32)), lo = (unsigned)dpp<CTRL>((int)v);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// After the xor-1 and xor-2 steps all four lanes of a quad agree, so the two
+// mirror steps act as xor-4 and xor-8: every lane ends with its group's total.
+template <int LANES> __device__ inline double group_sum(double a)
+{
+    a += dpp<DPP_XOR1>(a);
+    a += dpp<DPP_XOR2>(a);
+    if (LANES >= 8) a += dpp<DPP_HALF_MIRROR>(a);
+    if (LANES >= 16) a += dpp<DPP_MIRROR>(a);
+    if (LANES >= 32) a += __shfl_xor(a, 16, 64);
+    if (LANES >= 64) a += __shfl_xor(a, 32, 64);
+    return a;
+}
+__device__ inline double row_max(double a)
+{
+    a = fmax(a, dpp<DPP_XOR1>(a));
+    a = fmax(a, dpp<DPP_XOR2>(a));
+    a = fmax(a, dpp<DPP_HALF_MIRROR>(a));
+    return fmax(a, dpp<DPP_MIRROR>(a));
+}
+__device__ inline unsigned long long umin64(unsigned long long a, unsigned long long b)
+{
+    return a < b ? a : b;
+}
+__device__ inline unsigned long long row_min(unsigned long long a)
+{
+    a = umin64(a, dpp<DPP_XOR1>(a));
+    a = umin64(a, dpp<DPP_XOR2>(a));
+    a = umin64(a, dpp<DPP_HALF_MIRROR>(a));
+    return umin64(a, dpp<DPP_MIRROR>(a));
+}
+// value of lane L of the wave, as a wave-uniform scalar
+__device__ inline double lane_value(double v, int L)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), L),
+                            __builtin_amdgcn_readlane(__double2loint(v), L));
+}
+__device__ inline unsigned long long lane_value(unsigned long long v, int L)
+{
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(v >> 32), L);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)v, L);
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ inline double wave_max(double v)
+{
+    v = row_max(v);
+    return fmax(fmax(lane_value(v, 0), lane_value(v, 16)), fmax(lane_value(v, 32), lane_value(v, 48)));
+}
+__device__ inline double wave_sum(double v)
+{
+    v = group_sum<16>(v);
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+__device__ inline unsigned long long wave_min(unsigned long long v)
+{
+    v = row_min(v);
+    return umin64(umin64(lane_value(v, 0), lane_value(v, 16)),
+                  umin64(lane_value(v, 32), lane_value(v, 48)));
+}
+constexpr unsigned long long NO_CANDIDATE = ~0ull;
+
+template <int DT, int D, int NW, int U>
+__global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
+    char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
+    int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
+    const char *__restrict__ kn_g, const char *__restrict__ vn_g,
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale)
+{
+    // k: slots per head (stride); n_occ: occupied slots, always the prefix
+    // [0, n_occ) of the head's slots (slots fill in index order and are only
+    // ever overwritten in place); t: position of the token being generated.
+    using E = Elem<DT>;
+    using T = typename E::T;
+    constexpr int EPL = E::EPL;          // elements per lane per 16-byte load
+    constexpr int LPR = D / EPL;         // lanes per row
+    constexpr int RPW = 64 / LPR;        // rows per wave per load
+    constexpr int NT = NW * 64;
+    constexpr int RPI = NW * RPW;        // rows per workgroup-wide round
+    constexpr unsigned ROWB = D * sizeof(T);
+    static_assert(LPR >= 8 && LPR <= 32, "a row is read by 8, 16 or 32 lanes");
+
+    const int head = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane / LPR, li = lane % LPR;
+    const int kp = (k + 2) & ~1;         // keeps the arrays 8-byte aligned
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *s_l = reinterpret_cast<double *>(smem);            // [kp] logits, then exp
+    float *p_l = reinterpret_cast<float *>(s_l + kp);          // [kp] probabilities
+    float *acc_l = p_l + kp;                                   // [kp] updated scores
+    int *pos_l = reinterpret_cast<int *>(acc_l + kp);          // [kp]
+    float *o_l = reinterpret_cast<float *>(pos_l + kp);        // [NW][D]
+    double *red_max = reinterpret_cast<double *>(o_l + NW * D);
+    double *red_sum = red_max + NW;
+    unsigned long long *red_key = reinterpret_cast<unsigned long long *>(red_sum + NW);
+    int *target_l = reinterpret_cast<int *>(red_key + NW);     // [1]
+
+    const size_t hoff = (size_t)head * k;
+    const char *Kb = Kc + hoff * ROWB;                         // uniform bases
+    const char *Vb = Vc + hoff * ROWB;
+    const T *qh = reinterpret_cast<const T *>(q_g) + (size_t)head * D;
+    const T *knh = reinterpret_cast<const T *>(kn_g) + (size_t)head * D;
+    const T *vnh = reinterpret_cast<const T *>(vn_g) + (size_t)head * D;
+
+    const int rounds = (n_occ + RPI - 1) / RPI;
+    const int row0 = wave * RPW + sub;   // this lane's row inside a round
+    const int vbase = (rounds + U - 1) / U * U;   // stream index of value round 0
+    // stream entry e: key round e for e < rounds, value round e - vbase for
+    // vbase <= e < vbase + rounds, nothing in between; entry e lives in buf[e % U]
+    auto load_row = [&](const char *base, int round) -> uint4 {
+        const unsigned rc = (unsigned)min(round * RPI + row0, n_occ - 1);   // clamp: stays in bounds
+        return *reinterpret_cast<const uint4 *>(base + (rc * ROWB + (unsigned)li * 16u));
+    };
+
+    uint4 buf[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (u < rounds) buf[u] = load_row(Kb, u);
+
+    // this thread's share of the slot bookkeeping (slots tid, tid + NT, ...):
+    // the first JR entries are requested now, behind the key stream
+    constexpr int JR = 2;
+    int pos_r[JR];
+    float acc_r[JR];
+#pragma unroll
+    for (int i = 0; i < JR; ++i) {
+        const int j = tid + i * NT;
+        pos_r[i] = j < n_occ ? pos_g[hoff + j] : -1;
+        acc_r[i] = j < n_occ ? acc_g[hoff + j] : 0.f;
+    }
+
+    // this lane's slice of q (widened exactly) and the token's own logit
+    double qd[EPL];
+    double s_self;
+    {
+        const uint4 qraw = *reinterpret_cast<const uint4 *>(qh + li * EPL);
+        const uint4 kraw = *reinterpret_cast<const uint4 *>(knh + li * EPL);
+        const T *qe = reinterpret_cast<const T *>(&qraw);
+        const T *ke = reinterpret_cast<const T *>(&kraw);
+        double a = 0.0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            qd[i] = (double)E::to_f(qe[i]);
+            a = fma((double)E::to_f(ke[i]), qd[i], a);
+        }
+        s_self = group_sum<LPR>(a) * scale;
+    }
+
+    // ---- logits: one pass over the cached keys --------------------------------
+    // m_run: running maximum of this lane group's logits (the softmax shift)
+    double m_run = s_self;
+    for (int r = 0; r < rounds; r += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = r + u;
+            if (e < rounds) {
+                const T *x = reinterpret_cast<const T *>(&buf[u]);
+                double a = 0.0;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) a = fma((double)E::to_f(x[i]), qd[i], a);
+                const int nx = e + U;
+                if (nx < rounds) buf[u] = load_row(Kb, nx);
+                else if (nx >= vbase && nx - vbase < rounds) buf[u] = load_row(Vb, nx - vbase);
+                a = group_sum<LPR>(a) * scale;
+                const int row = e * RPI + row0;
+                if (li == 0 && row < n_occ) s_l[row] = a;
+                m_run = fmax(m_run, a);          // clamped duplicates repeat a real row
+            }
+            __builtin_amdgcn_sched_barrier(0);   // one row at a time: bounds live registers
+        }
+    }
+    {
+        // value rounds the ring has not requested yet (the ring positions that
+        // held no entry between the last key round and value round 0)
+        const int primed = rounds + U - vbase;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (u >= primed && u < rounds) buf[u] = load_row(Vb, u);
+    }
+    {
+        const double mw = wave_max(m_run);
+        if (lane == 0) red_max[wave] = mw;
+    }
+#pragma unroll
+    for (int i = 0; i < JR; ++i) {
+        const int j = tid + i * NT;
+        if (j < n_occ) { pos_l[j] = pos_r[i]; acc_l[j] = acc_r[i]; }
+    }
+    for (int j = tid + JR * NT; j < n_occ; j += NT) {
+        pos_l[j] = pos_g[hoff + j];
+        acc_l[j] = acc_g[hoff + j];
+    }
+    lds_barrier();
+
+    // ---- exact softmax over the occupied slots + the token itself -------------
+    // (slot j's bookkeeping is always handled by thread j % NT, so pos_l / acc_l
+    // entries are only ever touched by the thread that wrote them)
+    double mx = red_max[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mx = fmax(mx, red_max[w]);
+
+    double d_loc = 0.0;
+    for (int j = tid; j < n_occ; j += NT) {
+        const double e = exp(s_l[j] - mx);
+        s_l[j] = e;
+        d_loc += e;
+    }
+    const double e_self = exp(s_self - mx);
+    {
+        const double dw = wave_sum(d_loc);
+        if (lane == 0) red_sum[wave] = dw;
+    }
+    lds_barrier();
+    double den = e_self;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) den += red_sum[w];
+    const float p_self = (float)(e_self / den);
+
+    // ---- probabilities, score update, eviction candidates ---------------------
+    unsigned long long key = NO_CANDIDATE;
+    const int last_cand = t - recent;    // window after this step = {t-R+1 .. t}
+    for (int j = tid; j < n_occ; j += NT) {
+        const float p = (float)(s_l[j] / den);
+        p_l[j] = p;
+        const float a = acc_l[j] + p;                     // binary32 accumulate
+        acc_l[j] = a;
+        const int pj = pos_l[j];
+        if (pj <= last_cand)
+            key = umin64(key, ((unsigned long long)__float_as_uint(a) << 32) | (unsigned)pj);
+    }
+    {
+        const unsigned long long kw = wave_min(key);
+        if (lane == 0) red_key[wave] = kw;
+        if (tid == 0) *target_l = n_occ < k ? n_occ : -1;
+    }
+    lds_barrier();
+    key = red_key[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) key = umin64(key, red_key[w]);
+    // Which slot receives the new token: the first free one if any; else the
+    // evicted one.  With recent == 0 the token itself competes with its first
+    // score and may lose, in which case nothing is written (target stays -1).
+    if (n_occ >= k) {
+        const unsigned long long self_key =
+            ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
+        if (recent != 0 || key < self_key) {
+            const int wpos = (int)(unsigned)(key & 0xffffffffu);
+            for (int j = tid; j < n_occ; j += NT)
+                if (pos_l[j] == wpos) *target_l = j;      // positions are unique
+        }
+    }
+
+    // ---- output: one pass over the cached values ------------------------------
+    float o[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+    for (int r = 0; r < rounds; r += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int vr = r + u;
+            if (vr < rounds) {
+                const int row = vr * RPI + row0;
+                const float p = row < n_occ ? p_l[row] : 0.f;   // clamped duplicates add nothing
+                const uint4 raw = buf[u];
+                const int nx = vr + U;
+                if (nx < rounds) buf[u] = load_row(Vb, nx);
+                const T *x = reinterpret_cast<const T *>(&raw);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, E::to_f(x[i]), o[i]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) o[i] += __shfl_xor(o[i], m, 64);
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) o_l[wave * D + li * EPL + i] = o[i];
+    }
+    lds_barrier();
+
+    // ---- write-back: output, scores, and the new token into its slot ----------
+    const int target = *target_l;
+    if (tid < D) {
+        float r = p_self * E::to_f(vnh[tid]);
+#pragma unroll
+        for (int w = 0; w < NW; ++w) r += o_l[w * D + tid];
+        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r);
+    }
+    for (int j = tid; j < n_occ; j += NT)
+        if (j != target) acc_g[hoff + j] = acc_l[j];
+    if (target >= 0 && tid == 0) acc_g[hoff + target] = p_self;
+    if (target >= 0) {
+        if (tid == 0) pos_g[hoff + target] = t;
+        if (wave == NW - 1) {            // a wave that is not busy with the output row
+            if (lane < LPR) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(knh + lane * EPL);
+                *reinterpret_cast<uint4 *>(const_cast<char *>(Kb) + (size_t)target * ROWB + lane * 16) = v;
+            } else if (lane < 2 * LPR) {
+                const int l2 = lane - LPR;
+                const uint4 v = *reinterpret_cast<const uint4 *>(vnh + l2 * EPL);
+                *reinterpret_cast<uint4 *>(const_cast<char *>(Vb) + (size_t)target * ROWB + l2 * 16) = v;
+            }
+        }
+    }
+}
+
+template <int DT, int D, int NW, int U>
+hipError_t launch(const h2o_cache &c, const void *q, const void *kn, const void *vn, void *out,
+                  hipStream_t st)
+{
+    const int k = c.k;
+    const int kp = (k + 2) & ~1;
+    const size_t smem = (size_t)kp * 20 + (size_t)NW * D * 4 + (size_t)NW * 28 + 16;
+    auto kern = decode_kernel<DT, D, NW, U>;
+    if (smem > 48 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               150 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    const int heads = c.cfg.batch * c.cfg.heads;
+    hipLaunchKernelGGL(kern, dim3(heads), dim3(NW * 64), smem, st, c.K, c.V, c.acc, c.pos,
+                       static_cast<const char *>(q), static_cast<const char *>(kn),
+                       static_cast<const char *>(vn), static_cast<char *>(out), k,
+                       c.t < k ? c.t : k, c.t, c.cfg.recent, c.scale);
+    return hipGetLastError();
+}
+
+template <int DT, int D>
+hipError_t pick(const h2o_cache &c, const void *q, const void *kn, const void *vn, void *out,
+                hipStream_t st)
+{
+    // Waves per head and ring depth follow the budget: the ring should hold all
+    // key rounds when it can (then every value row is requested before the
+    // softmax), and small budgets use 4 waves so more heads share a CU.
+    constexpr int LPR = D / Elem<DT>::EPL;
+    constexpr int RPW = 64 / LPR;
+    const int k = c.t < c.k ? c.t : c.k;      // occupied slots
+    if (k <= 4 * RPW * 13) {
+        const int rounds = (k + 4 * RPW - 1) / (4 * RPW);
+        if (rounds <= 4) return launch<DT, D, 4, 4>(c, q, kn, vn, out, st);
+        if (rounds <= 8) return launch<DT, D, 4, 8>(c, q, kn, vn, out, st);
+        return launch<DT, D, 4, 13>(c, q, kn, vn, out, st);
+    }
+    const int rounds = (k + 8 * RPW - 1) / (8 * RPW);
+    if (rounds <= 8) return launch<DT, D, 8, 8>(c, q, kn, vn, out, st);
+    return launch<DT, D, 8, 13>(c, q, kn, vn, out, st);
+}
+
+}  // namespace
+
+hipError_t h2o_launch_decode(const h2o_cache &c, const void *q, const void *k_new,
+                             const void *v_new, void *out, hipStream_t st)
+{
+    const int d = c.cfg.head_dim;
+    switch (c.cfg.dtype) {
+    case H2O_F32:
+        return d == 64 ? pick<H2O_F32, 64>(c, q, k_new, v_new, out, st)
+                       : pick<H2O_F32, 128>(c, q, k_new, v_new, out, st);
+    case H2O_F16:
+        return d == 64 ? pick<H2O_F16, 64>(c, q, k_new, v_new, out, st)
+                       : pick<H2O_F16, 128>(c, q, k_new, v_new, out, st);
+    default:
+        return d == 64 ? pick<H2O_BF16, 64>(c, q, k_new, v_new, out, st)
+                       : pick<H2O_BF16, 128>(c, q, k_new, v_new, out, st);
+    }
+}

@@ -1,0 +1,216 @@
+// C ABI of the H2O hot path (declarations and contracts: include/h2o.h).
+// Host-side only: argument validation, carving the caller's device memory into
+// the four cache regions, state tracking (tokens seen), kernel launches.
+#include <new>
+#include "h2o_internal.h"
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_config(const h2o_config *c)
+{
+    if (!c) return H2O_EINVAL;
+    if (c->batch < 1 || c->heads < 1 || c->heavy < 0 || c->recent < 0) return H2O_EINVAL;
+    if ((int64_t)c->heavy + c->recent < 1) return H2O_EINVAL;
+    if (c->dtype != H2O_F32 && c->dtype != H2O_F16 && c->dtype != H2O_BF16) return H2O_EINVAL;
+    if (!(c->scale >= 0.0f) || !(c->scale < 3.0e38f)) return H2O_EINVAL;
+    if (c->head_dim != 64 && c->head_dim != 128) return H2O_EUNSUPPORTED;
+    if ((int64_t)c->heavy + c->recent > H2O_MAX_BUDGET) return H2O_EUNSUPPORTED;
+    if ((int64_t)c->batch * c->heads > (1 << 24)) return H2O_EUNSUPPORTED;
+    return H2O_OK;
+}
+
+struct Layout { size_t kv, acc_off, pos_off, total; };
+
+Layout layout_of(const h2o_config &c)
+{
+    const size_t heads = (size_t)c.batch * c.heads, k = (size_t)c.heavy + c.recent;
+    Layout l;
+    l.kv = align_up(heads * k * c.head_dim * h2o_esize(c.dtype), 256);
+    l.acc_off = 2 * l.kv;
+    l.pos_off = l.acc_off + align_up(heads * k * sizeof(float), 256);
+    l.total = l.pos_off + align_up(heads * k * sizeof(int32_t), 256);
+    return l;
+}
+
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? H2O_OK : H2O_EHIP; }
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+size_t h2o_cache_bytes(const h2o_config *cfg)
+{
+    if (check_config(cfg) != H2O_OK) return 0;
+    return layout_of(*cfg).total;
+}
+
+size_t h2o_prefill_workspace_bytes(const h2o_config *cfg, int32_t n)
+{
+    if (check_config(cfg) != H2O_OK || n < 1 || n > H2O_MAX_PROMPT) return 0;
+    const size_t heads = (size_t)cfg->batch * cfg->heads;
+    return 2 * align_up(heads * (size_t)n * sizeof(float), 256);
+}
+
+int h2o_cache_init(const h2o_config *cfg, void *dev_mem, size_t bytes, void *hip_stream,
+                   h2o_cache **out)
+{
+    if (out) *out = nullptr;
+    const int rc = check_config(cfg);
+    if (rc != H2O_OK) return rc;
+    if (!dev_mem || !out || !aligned16(dev_mem)) return H2O_EINVAL;
+    const Layout l = layout_of(*cfg);
+    if (bytes < l.total) return H2O_ENOMEM;
+    h2o_cache *c = new (std::nothrow) h2o_cache;
+    if (!c) return H2O_ENOMEM;
+    c->cfg = *cfg;
+    c->scale = h2o_scale_of(*cfg);
+    c->k = cfg->heavy + cfg->recent;
+    c->esize = h2o_esize(cfg->dtype);
+    c->t = 0;
+    char *base = static_cast<char *>(dev_mem);
+    c->K = base;
+    c->V = base + l.kv;
+    c->acc = reinterpret_cast<float *>(base + l.acc_off);
+    c->pos = reinterpret_cast<int32_t *>(base + l.pos_off);
+    c->kv_bytes = (size_t)cfg->batch * cfg->heads * c->k * cfg->head_dim * c->esize;
+    const hipError_t e = h2o_launch_mark_free(*c, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) { delete c; return H2O_EHIP; }
+    *out = c;
+    return H2O_OK;
+}
+
+int h2o_cache_reset(h2o_cache *cache, void *hip_stream)
+{
+    if (!cache) return H2O_EINVAL;
+    const hipError_t e = h2o_launch_mark_free(*cache, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return H2O_EHIP;
+    cache->t = 0;
+    return H2O_OK;
+}
+
+void h2o_cache_destroy(h2o_cache *cache) { delete cache; }
+
+int h2o_prefill_colsum(const h2o_config *cfg, const void *Q, const void *K, int32_t n,
+                       void *workspace, size_t ws_bytes, float *colsum_out, void *hip_stream)
+{
+    const int rc = check_config(cfg);
+    if (rc != H2O_OK) return rc;
+    if (!Q || !K || !workspace || !colsum_out || n < 1) return H2O_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(workspace) || !aligned16(colsum_out))
+        return H2O_EINVAL;
+    if (n > H2O_MAX_PROMPT) return H2O_EUNSUPPORTED;
+    if (ws_bytes < h2o_prefill_workspace_bytes(cfg, n)) return H2O_ENOMEM;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    float *lse = static_cast<float *>(workspace);
+    const double scale = h2o_scale_of(*cfg);
+    hipError_t e = h2o_launch_prefill_lse(*cfg, scale, Q, K, n, lse, st);
+    if (e != hipSuccess) return H2O_EHIP;
+    e = h2o_launch_prefill_colsum(*cfg, scale, Q, K, n, lse, colsum_out, st);
+    return hip_rc(e);
+}
+
+int h2o_prefill_select(h2o_cache *cache, const void *K, const void *V, const float *score,
+                       int32_t n, void *hip_stream)
+{
+    if (!cache || !K || !V || !score || n < 1) return H2O_EINVAL;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(score)) return H2O_EINVAL;
+    if (n > H2O_MAX_PROMPT) return H2O_EUNSUPPORTED;
+    if (cache->t != 0) return H2O_ESTATE;
+    const hipError_t e =
+        h2o_launch_select_gather(*cache, K, V, score, n, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return H2O_EHIP;
+    cache->t = n;
+    return H2O_OK;
+}
+
+int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K, const void *V, int32_t n,
+                       void *workspace, size_t ws_bytes, float *colsum_out, void *hip_stream)
+{
+    if (!cache || !V) return H2O_EINVAL;
+    if (cache->t != 0) return H2O_ESTATE;
+    if (n < 1) return H2O_EINVAL;
+    if (n > H2O_MAX_PROMPT) return H2O_EUNSUPPORTED;
+    const size_t need = h2o_prefill_workspace_bytes(&cache->cfg, n);
+    if (!workspace || ws_bytes < need) return workspace ? H2O_ENOMEM : H2O_EINVAL;
+    // second half of the workspace holds the sums unless the caller wants them
+    float *sums = colsum_out ? colsum_out
+                             : reinterpret_cast<float *>(static_cast<char *>(workspace) + need / 2);
+    int rc = h2o_prefill_colsum(&cache->cfg, Q, K, n, workspace, ws_bytes, sums, hip_stream);
+    if (rc != H2O_OK) return rc;
+    return h2o_prefill_select(cache, K, V, sums, n, hip_stream);
+}
+
+int h2o_decode_step(h2o_cache *cache, const void *q, const void *k_new, const void *v_new,
+                    void *out, void *hip_stream)
+{
+    if (!cache || !q || !k_new || !v_new || !out) return H2O_EINVAL;
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out))
+        return H2O_EINVAL;
+    if (cache->t >= 0x7ffffff0) return H2O_EUNSUPPORTED;
+    const hipError_t e =
+        h2o_launch_decode(*cache, q, k_new, v_new, out, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return H2O_EHIP;
+    cache->t += 1;
+    return H2O_OK;
+}
+
+int h2o_cache_snapshot(const h2o_cache *cache, int32_t *pos_out, float *acc_out, void *hip_stream)
+{
+    if (!cache) return H2O_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const size_t cnt = (size_t)cache->cfg.batch * cache->cfg.heads * cache->k;
+    if (pos_out &&
+        hipMemcpyAsync(pos_out, cache->pos, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return H2O_EHIP;
+    if (acc_out &&
+        hipMemcpyAsync(acc_out, cache->acc, cnt * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return H2O_EHIP;
+    return H2O_OK;
+}
+
+int h2o_cache_restore(h2o_cache *cache, const void *K, const void *V, const float *acc,
+                      const int32_t *pos, int32_t tokens_seen, void *hip_stream)
+{
+    if (!cache || !K || !V || !acc || !pos || tokens_seen < 0) return H2O_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const size_t cnt = (size_t)cache->cfg.batch * cache->cfg.heads * cache->k;
+    if (hipMemcpyAsync(cache->K, K, cache->kv_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+        hipMemcpyAsync(cache->V, V, cache->kv_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+        hipMemcpyAsync(cache->acc, acc, cnt * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess ||
+        hipMemcpyAsync(cache->pos, pos, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return H2O_EHIP;
+    cache->t = tokens_seen;
+    return H2O_OK;
+}
+
+int h2o_cache_tokens_seen(const h2o_cache *cache) { return cache ? cache->t : H2O_EINVAL; }
+
+int h2o_cache_regions(const h2o_cache *cache, void **K, void **V, float **acc, int32_t **pos)
+{
+    if (!cache) return H2O_EINVAL;
+    if (K) *K = cache->K;
+    if (V) *V = cache->V;
+    if (acc) *acc = cache->acc;
+    if (pos) *pos = cache->pos;
+    return H2O_OK;
+}
+
+const char *h2o_status_str(int status)
+{
+    switch (status) {
+    case H2O_OK: return "ok";
+    case H2O_EINVAL: return "invalid argument";
+    case H2O_EUNSUPPORTED: return "unsupported configuration";
+    case H2O_ENOMEM: return "caller buffer too small";
+    case H2O_ESTATE: return "call not legal in this cache state";
+    case H2O_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,65 @@
+// Internal declarations shared by the translation units of the HIP library.
+// Not part of the public ABI (see include/h2o.h for that).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "h2o.h"
+
+struct h2o_cache {
+    h2o_config cfg;
+    double scale;      // logit scale actually used (cfg.scale, or 1/sqrt(d) in double)
+    int k;             // heavy + recent
+    int esize;         // bytes per element of K/V
+    int t;             // tokens seen so far
+    char *K;           // [B*Hh][k][d]
+    char *V;           // [B*Hh][k][d]
+    float *acc;        // [B*Hh][k]
+    int32_t *pos;      // [B*Hh][k]
+    size_t kv_bytes;   // bytes of the K (= V) region
+};
+
+static inline int h2o_esize(int dtype) { return dtype == H2O_F32 ? 4 : 2; }
+static inline double h2o_scale_of(const h2o_config &c)
+{
+    return c.scale != 0.0f ? (double)c.scale : 1.0 / sqrt((double)c.head_dim);
+}
+
+// ---- kernel launchers (each enqueues on `st` and returns hipGetLastError()) ----
+hipError_t h2o_launch_mark_free(const h2o_cache &c, hipStream_t st);
+hipError_t h2o_launch_decode(const h2o_cache &c, const void *q, const void *k_new,
+                             const void *v_new, void *out, hipStream_t st);
+hipError_t h2o_launch_prefill_lse(const h2o_config &cfg, double scale, const void *Q,
+                                  const void *K, int n, float *lse, hipStream_t st);
+hipError_t h2o_launch_prefill_colsum(const h2o_config &cfg, double scale, const void *Q,
+                                     const void *K, int n, const float *lse, float *colsum,
+                                     hipStream_t st);
+hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const void *V,
+                                    const float *score, int n, hipStream_t st);
+
+// ---- element types ----------------------------------------------------------
+// Raw storage views: f32 -> float, f16 -> _Float16, bf16 -> uint16_t bit pattern.
+template <int DT> struct Elem;
+template <> struct Elem<H2O_F32> {
+    using T = float;
+    static constexpr int EPL = 4;   // elements per 16-byte lane load
+    __device__ static inline float to_f(T v) { return v; }
+    __device__ static inline T from_f(float v) { return v; }
+};
+template <> struct Elem<H2O_F16> {
+    using T = _Float16;
+    static constexpr int EPL = 8;
+    __device__ static inline float to_f(T v) { return (float)v; }
+    __device__ static inline T from_f(float v) { return (T)v; }   // round-to-nearest-even
+};
+template <> struct Elem<H2O_BF16> {
+    using T = uint16_t;
+    static constexpr int EPL = 8;
+    __device__ static inline float to_f(T v) { return __uint_as_float(((uint32_t)v) << 16); }
+    __device__ static inline T from_f(float v)
+    {
+        uint32_t u = __float_as_uint(v);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (T)((u >> 16) | 0x40u);   // NaN stays NaN
+        u += 0x7fffu + ((u >> 16) & 1u);                                      // nearest-even
+        return (T)(u >> 16);
+    }
+};

@@ -1,0 +1,260 @@
+// Prompt scoring for H2O on gfx950 (MFMA): the column sums of the prompt's
+// causal softmax matrix, which seed the accumulated attention scores
+// (exact generative process of App. D "Eviction policy"; Algorithm 2's
+// accumulate line applied to every prompt row).
+//
+//   pass 1 (row statistics) : LSE_i = log sum_{j<=i} exp(scale * <Q_i, K_j>)
+//   pass 2 (column sums)    : c_j   = sum_{i>=j} exp(scale * <Q_i, K_j> - LSE_i)
+//
+// Both passes are the same dense contraction QK^T and run on the matrix cores;
+// they differ in which operand stays in registers.  A workgroup of 4 waves owns
+// 128 "stationary" rows (queries in pass 1, keys in pass 2; 32 per wave, kept in
+// registers as MFMA B-operand fragments) and streams tiles of the other operand
+// through LDS (double buffered) as A-operand fragments.  With the 32x32 MFMA
+// result layout a lane then holds one stationary row's products with 16 streamed
+// rows per tile, so the reduction each pass needs (over keys for the row
+// statistics, over queries for the column sums) runs inside a lane across the
+// whole stream and needs no cross-lane traffic and no atomics; the two lane
+// halves are merged once at the end.
+//
+// Everything is computed in base 2: x = (scale*log2 e) * <q,k>, the stored row
+// statistic is log2 of the row's normaliser.
+#include "h2o_internal.h"
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int SROWS = 128;     // stationary rows per workgroup (4 waves x 32)
+
+template <int DT>
+__device__ inline f32x16 mma(const uint4 &a, const uint4 &b, f32x16 acc)
+{
+    if constexpr (DT == H2O_BF16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            *reinterpret_cast<const bf16x8 *>(&a), *reinterpret_cast<const bf16x8 *>(&b), acc, 0, 0, 0);
+    } else if constexpr (DT == H2O_F16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(
+            *reinterpret_cast<const f16x8 *>(&a), *reinterpret_cast<const f16x8 *>(&b), acc, 0, 0, 0);
+    } else {
+        const float *af = reinterpret_cast<const float *>(&a);
+        const float *bf = reinterpret_cast<const float *>(&b);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[e], bf[e], acc, 0, 0, 0);
+        return acc;
+    }
+}
+
+// DT: element type; D: head_dim; MB: 32-row blocks per streamed tile;
+// COLSUM: false = pass 1 (row statistics), true = pass 2 (column sums).
+template <int DT, int D, int MB, bool COLSUM>
+__global__ __launch_bounds__(256) void prefill_pass_kernel(
+    const char *__restrict__ Qg, const char *__restrict__ Kg, int n, int heads, float c2,
+    float *__restrict__ lse2, float *__restrict__ colsum)
+{
+    constexpr int ES = DT == H2O_F32 ? 4 : 2;
+    constexpr int ROWB = D * ES;          // bytes per row
+    constexpr int NF = ROWB / 32;         // 16-byte fragments per row per lane half
+    constexpr int BN = 32 * MB;           // streamed rows per tile
+    constexpr int LROW = ROWB + 16;       // padded LDS row pitch (bank spread)
+    constexpr int TILEB = BN * LROW;
+    constexpr int CPR = ROWB / 16;        // 16-byte chunks per row
+    constexpr int CHUNKS = BN * CPR;      // 16-byte chunks per tile
+    constexpr int CPT = (CHUNKS + 255) / 256;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *tile_l = smem;                                      // [2][TILEB]
+    float *lse_l = reinterpret_cast<float *>(smem + 2 * TILEB);        // [2][BN] (pass 2)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int nblk = (n + SROWS - 1) / SROWS;
+    const int head = blockIdx.x % heads;
+    const int ord = blockIdx.x / heads;
+    // heaviest blocks first: pass 1's last row block sees every key tile,
+    // pass 2's first key block sees every query tile
+    const int blk = COLSUM ? ord : nblk - 1 - ord;
+    const int s0 = blk * SROWS;
+    const size_t hbase = (size_t)head * n * ROWB;
+    const char *Sg = (COLSUM ? Kg : Qg) + hbase;     // stationary operand
+    const char *Tg = (COLSUM ? Qg : Kg) + hbase;     // streamed operand
+    const float *lse_h = lse2 + (size_t)head * n;
+
+    const int srow = s0 + wave * 32 + l32;           // this lane's stationary row
+    uint4 st[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        st[f] = make_uint4(0, 0, 0, 0);
+        if (srow < n)
+            st[f] = *reinterpret_cast<const uint4 *>(Sg + (size_t)srow * ROWB + (2 * f + half) * 16);
+    }
+
+    const int ntile_all = (n + BN - 1) / BN;
+    const int t_begin = COLSUM ? s0 / BN : 0;
+    const int t_end = COLSUM ? ntile_all : min(ntile_all, (s0 + SROWS + BN - 1) / BN);
+
+    uint4 g[CPT];
+    float gl = 0.f;
+    auto fetch = [&](int tile) {
+        const int r0 = tile * BN;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const int ch = tid + c * 256;
+            const int r = ch / CPR, cc = ch % CPR;
+            g[c] = make_uint4(0, 0, 0, 0);
+            if (ch < CHUNKS && r0 + r < n)
+                g[c] = *reinterpret_cast<const uint4 *>(Tg + (size_t)(r0 + r) * ROWB + cc * 16);
+        }
+        if (COLSUM && tid < BN) gl = (r0 + tid < n) ? lse_h[r0 + tid] : INFINITY;
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const int ch = tid + c * 256;
+            const int r = ch / CPR, cc = ch % CPR;
+            if (ch < CHUNKS)
+                *reinterpret_cast<uint4 *>(tile_l + buf * TILEB + r * LROW + cc * 16) = g[c];
+        }
+        if (COLSUM && tid < BN) lse_l[buf * BN + tid] = gl;
+    };
+
+    float m_run = -INFINITY, l_run = 0.f;   // pass 1: running max / sum (base 2)
+    float c_run = 0.f;                      // pass 2: running column sum
+
+    if (t_begin < t_end) { fetch(t_begin); stash(0); }
+    __syncthreads();
+
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        const int buf = (tile - t_begin) & 1;
+        const bool more = tile + 1 < t_end;
+        if (more) fetch(tile + 1);
+
+        f32x16 acc[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+        const unsigned char *tb = tile_l + buf * TILEB;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const uint4 a = *reinterpret_cast<const uint4 *>(
+                    tb + (mb * 32 + l32) * LROW + (2 * f + half) * 16);
+                acc[mb] = mma<DT>(a, st[f], acc[mb]);
+            }
+        }
+
+        const int r0 = tile * BN;
+        if constexpr (!COLSUM) {
+            // streamed rows are keys j, this lane's row is query i = srow: need j <= i
+            const bool diag = r0 + BN - 1 > s0;          // tile may cross the diagonal
+            float mx = m_run;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    float x = acc[mb][v] * c2;
+                    if (diag && j > srow) x = -INFINITY;
+                    acc[mb][v] = x;
+                    mx = fmaxf(mx, x);
+                }
+            const float ms = mx == -INFINITY ? 0.f : mx;
+            float sum = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(acc[mb][v] - ms);
+            l_run = l_run * __builtin_amdgcn_exp2f(m_run - ms) + sum;
+            m_run = mx;
+        } else {
+            // streamed rows are queries i, this lane's row is key j = srow: need i >= j
+            const bool diag = r0 < s0 + SROWS - 1;
+            const float *ll = lse_l + buf * BN;
+            float sum = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const float4 l4 = *reinterpret_cast<const float4 *>(ll + mb * 32 + 8 * gq + 4 * half);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = r0 + mb * 32 + 8 * gq + 4 * half + e;
+                        float x = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);   // rows past n: -inf
+                        if (diag && i < srow) x = -INFINITY;
+                        sum += __builtin_amdgcn_exp2f(x);
+                    }
+                }
+            c_run += sum;
+        }
+
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    if constexpr (!COLSUM) {
+        const float m2 = __shfl_xor(m_run, 32, 64), l2 = __shfl_xor(l_run, 32, 64);
+        const float M = fmaxf(m_run, m2);            // finite: key 0 is visible to every query
+        const float L = l_run * __builtin_amdgcn_exp2f(m_run - M) + l2 * __builtin_amdgcn_exp2f(m2 - M);
+        if (half == 0 && srow < n) lse2[(size_t)head * n + srow] = M + __builtin_amdgcn_logf(L);
+    } else {
+        const float c = c_run + __shfl_xor(c_run, 32, 64);
+        if (half == 0 && srow < n) colsum[(size_t)head * n + srow] = c;
+    }
+}
+
+template <int DT, int D, bool COLSUM>
+hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
+                       float *lse2, float *colsum, hipStream_t st)
+{
+    constexpr int ES = DT == H2O_F32 ? 4 : 2;
+    constexpr int MB = (D * ES >= 512) ? 1 : 2;      // keep the two tile buffers under 48 KiB
+    constexpr int BN = 32 * MB;
+    constexpr size_t smem = 2 * (size_t)BN * (D * ES + 16) + 2 * BN * sizeof(float);
+    static_assert(smem <= 48 * 1024, "tile buffers must fit the default LDS limit");
+    const int heads = cfg.batch * cfg.heads;
+    const int nblk = (n + SROWS - 1) / SROWS;
+    const float c2 = (float)(scale * 1.4426950408889634);
+    hipLaunchKernelGGL((prefill_pass_kernel<DT, D, MB, COLSUM>), dim3((unsigned)heads * nblk),
+                       dim3(256), smem, st, static_cast<const char *>(Q),
+                       static_cast<const char *>(K), n, heads, c2, lse2, colsum);
+    return hipGetLastError();
+}
+
+template <bool COLSUM>
+hipError_t dispatch(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
+                    float *lse2, float *colsum, hipStream_t st)
+{
+    const int d = cfg.head_dim;
+    switch (cfg.dtype) {
+    case H2O_F32:
+        return d == 64 ? launch_pass<H2O_F32, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_F32, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+    case H2O_F16:
+        return d == 64 ? launch_pass<H2O_F16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_F16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+    default:
+        return d == 64 ? launch_pass<H2O_BF16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_BF16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+    }
+}
+
+}  // namespace
+
+hipError_t h2o_launch_prefill_lse(const h2o_config &cfg, double scale, const void *Q,
+                                  const void *K, int n, float *lse, hipStream_t st)
+{
+    return dispatch<false>(cfg, scale, Q, K, n, lse, nullptr, st);
+}
+
+hipError_t h2o_launch_prefill_colsum(const h2o_config &cfg, double scale, const void *Q,
+                                     const void *K, int n, const float *lse, float *colsum,
+                                     hipStream_t st)
+{
+    return dispatch<true>(cfg, scale, Q, K, n, const_cast<float *>(lse), colsum, st);
+}

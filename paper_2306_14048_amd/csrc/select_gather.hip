@@ -1,0 +1,200 @@
+// Prompt compression for H2O on gfx950: given one score per prompt token, keep
+// the `recent` last tokens plus the `heavy` best-scoring older ones (or all n
+// tokens when n fits in the budget) and copy their key/value rows into the
+// cache slots in ascending position order (App. A: the prompt phase returns the
+// heavy hitters and the recent tokens, or everything for a short prompt).
+//
+// Selecting the `heavy` largest under the order (score, then position) is the
+// same as repeatedly evicting the smallest (score, position) pair, the rule the
+// generation steps use.  One workgroup per head: an exact 4x8-bit radix select
+// on the order-preserving integer image of the scores finds the threshold, the
+// positions of equal-score tokens break the tie at the threshold, a block scan
+// assigns slots, then all threads copy rows with 128-bit accesses.
+#include "h2o_internal.h"
+
+namespace {
+
+constexpr int SG_NT = 512;
+constexpr int SG_NW = SG_NT / 64;
+
+__device__ inline unsigned order_key(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // monotone in x
+}
+
+// Exclusive prefix sum of one int per thread over the workgroup; `total`
+// receives the sum.  `scratch` holds SG_NW + 1 ints.
+__device__ inline int block_exclusive_scan(int v, int *scratch, int &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += y;
+    }
+    __syncthreads();                       // scratch may still be read from a previous scan
+    if (lane == 63) scratch[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < SG_NW; ++w) {
+        const int s = scratch[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    total = tot;
+    return base + inc - v;
+}
+
+template <int ROWB>
+__global__ __launch_bounds__(SG_NT) void select_gather_kernel(
+    const char *__restrict__ Kp, const char *__restrict__ Vp, const float *__restrict__ score,
+    int n, char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
+    int32_t *__restrict__ pos_g, int k, int heavy, int recent)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    int *sel_l = reinterpret_cast<int *>(smem);        // [k] slot -> prompt position
+    __shared__ unsigned hist[256];
+    __shared__ unsigned sh_prefix, sh_need;
+    __shared__ int scan_l[SG_NW + 1];
+
+    const int head = blockIdx.x, tid = threadIdx.x;
+    const float *sc = score + (size_t)head * n;
+    const size_t hoff = (size_t)head * k;
+
+    for (int s = tid; s < k; s += SG_NT) sel_l[s] = -1;
+
+    if (n <= k) {
+        __syncthreads();
+        for (int s = tid; s < n; s += SG_NT) sel_l[s] = s;
+    } else {
+        const int older = n - recent;                  // candidates: positions [0, older)
+        unsigned thr = 0, need = 0;                    // keep keys > thr, and `need` of those == thr
+        if (heavy > 0) {
+            // radix select: the heavy-th largest key among the older tokens
+            unsigned prefix = 0, mask = 0;
+            need = (unsigned)heavy;
+            for (int shift = 24; shift >= 0; shift -= 8) {
+                for (int b = tid; b < 256; b += SG_NT) hist[b] = 0;
+                __syncthreads();
+                for (int j = tid; j < older; j += SG_NT) {
+                    const unsigned key = order_key(sc[j]);
+                    if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    unsigned cum = 0;
+                    int b = 255;
+                    for (; b > 0; --b) {
+                        if (cum + hist[b] >= need) break;
+                        cum += hist[b];
+                    }
+                    sh_prefix = prefix | ((unsigned)b << shift);
+                    sh_need = need - cum;              // still needed inside bin b
+                }
+                __syncthreads();
+                prefix = sh_prefix;
+                need = sh_need;
+                mask |= 255u << shift;
+                __syncthreads();
+            }
+            thr = prefix;
+        }
+        // each thread owns a contiguous run of positions so that ranks follow position order
+        const int per = (n + SG_NT - 1) / SG_NT;
+        const int j0 = min(n, tid * per), j1 = min(n, j0 + per);
+        int eq_cnt = 0;
+        if (heavy > 0)
+            for (int j = j0; j < min(j1, older); ++j) eq_cnt += order_key(sc[j]) == thr;
+        int eq_total;
+        int eq_before = block_exclusive_scan(eq_cnt, scan_l, eq_total);
+        // among equal scores the higher positions are kept: the last `need` of them
+        const int eq_first_kept = eq_total - (int)need;
+        int keep_cnt = 0;
+        {
+            int e = eq_before;
+            for (int j = j0; j < j1; ++j) {
+                bool keep = j >= older;
+                if (!keep && heavy > 0) {
+                    const unsigned key = order_key(sc[j]);
+                    if (key > thr) keep = true;
+                    else if (key == thr) { keep = e >= eq_first_kept; ++e; }
+                }
+                keep_cnt += keep;
+            }
+        }
+        int kept_total;
+        int slot = block_exclusive_scan(keep_cnt, scan_l, kept_total);
+        {
+            int e = eq_before;
+            for (int j = j0; j < j1; ++j) {
+                bool keep = j >= older;
+                if (!keep && heavy > 0) {
+                    const unsigned key = order_key(sc[j]);
+                    if (key > thr) keep = true;
+                    else if (key == thr) { keep = e >= eq_first_kept; ++e; }
+                }
+                if (keep) { if (slot < k) sel_l[slot] = j; ++slot; }
+            }
+        }
+    }
+    __syncthreads();
+
+    // bookkeeping of every slot
+    for (int s = tid; s < k; s += SG_NT) {
+        const int j = sel_l[s];
+        pos_g[hoff + s] = j;
+        acc_g[hoff + s] = j >= 0 ? sc[j] : 0.f;
+    }
+    // gather rows: LPR lanes copy one row of ROWB bytes
+    constexpr int LPR = ROWB / 16;
+    constexpr int ROWS_PER_ROUND = SG_NT / LPR;
+    const int li = tid % LPR, rsub = tid / LPR;
+    const size_t pbase = (size_t)head * n * ROWB;
+    for (int s = rsub; s < k; s += ROWS_PER_ROUND) {
+        const int j = sel_l[s];
+        if (j < 0) continue;
+        const uint4 kv = *reinterpret_cast<const uint4 *>(Kp + pbase + (size_t)j * ROWB + li * 16);
+        const uint4 vv = *reinterpret_cast<const uint4 *>(Vp + pbase + (size_t)j * ROWB + li * 16);
+        *reinterpret_cast<uint4 *>(Kc + (hoff + s) * ROWB + li * 16) = kv;
+        *reinterpret_cast<uint4 *>(Vc + (hoff + s) * ROWB + li * 16) = vv;
+    }
+}
+
+__global__ void mark_free_kernel(float *__restrict__ acc, int32_t *__restrict__ pos, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) { acc[i] = 0.f; pos[i] = -1; }
+}
+
+}  // namespace
+
+hipError_t h2o_launch_mark_free(const h2o_cache &c, hipStream_t st)
+{
+    const size_t count = (size_t)c.cfg.batch * c.cfg.heads * c.k;
+    const unsigned blocks = (unsigned)((count + 255) / 256);
+    hipLaunchKernelGGL(mark_free_kernel, dim3(blocks), dim3(256), 0, st, c.acc, c.pos, count);
+    return hipGetLastError();
+}
+
+hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const void *V,
+                                    const float *score, int n, hipStream_t st)
+{
+    const int heads = c.cfg.batch * c.cfg.heads;
+    const int rowb = c.cfg.head_dim * c.esize;
+    const size_t smem = (size_t)c.k * sizeof(int);
+    const char *Kp = static_cast<const char *>(K), *Vp = static_cast<const char *>(V);
+#define H2O_SG(RB)                                                                              \
+    hipLaunchKernelGGL((select_gather_kernel<RB>), dim3(heads), dim3(SG_NT), smem, st, Kp, Vp,   \
+                       score, n, c.K, c.V, c.acc, c.pos, c.k, c.cfg.heavy, c.cfg.recent)
+    switch (rowb) {
+    case 128: H2O_SG(128); break;
+    case 256: H2O_SG(256); break;
+    case 512: H2O_SG(512); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef H2O_SG
+    return hipGetLastError();
+}

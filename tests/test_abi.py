@@ -1,0 +1,95 @@
+"""The C-ABI library: it loads, exports every function the header declares, and
+its host-side argument checks answer without touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def hb():
+    lib = os.path.join(ROOT, "paper_2306_14048_amd", "libh2o_hip.so")
+    if not os.path.exists(lib):
+        from paper_2306_14048_amd import build
+        build.build(verbose=False)
+    from paper_2306_14048_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "h2o.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(h2o_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_and_library_agree(hb):
+    names = declared_functions()
+    assert len(names) >= 14
+    lib = ctypes.CDLL(hb.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), "library does not export %s" % n
+    assert sorted(hb.EXPORTS) == names, "python binding and header list different entry points"
+
+
+def test_size_queries_and_validation(hb):
+    ok = hb.make_config(16, 32, 128, 205, 205, hb.H2O_F16)
+    # K | V | acc | pos, each padded to 256 bytes
+    kv = 16 * 32 * 410 * 128 * 2
+    meta = 16 * 32 * 410 * 4
+    assert hb.h2o_cache_bytes(ok) == 2 * kv + 2 * meta
+    assert hb.h2o_prefill_workspace_bytes(ok, 2048) == 2 * 16 * 32 * 2048 * 4
+    bad = [hb.make_config(0, 32, 128, 4, 4, hb.H2O_F16), hb.make_config(1, 1, 96, 4, 4, hb.H2O_F16),
+           hb.make_config(1, 1, 128, 0, 0, hb.H2O_F16), hb.make_config(1, 1, 128, -1, 4, hb.H2O_F16),
+           hb.make_config(1, 1, 128, 4000, 4000, hb.H2O_F16), hb.make_config(1, 1, 128, 4, 4, 7)]
+    for c in bad:
+        assert hb.h2o_cache_bytes(c) == 0
+    assert hb.h2o_prefill_workspace_bytes(ok, 0) == 0
+    assert hb.h2o_prefill_workspace_bytes(ok, hb.H2O_MAX_PROMPT + 1) == 0
+
+
+def test_error_codes_without_device(hb):
+    lib = hb._lib
+    ok = hb.make_config(1, 1, 128, 4, 4, hb.H2O_F16)
+    out = ctypes.c_void_p()
+    assert lib.h2o_cache_init(None, 0x1000, 1 << 20, None, ctypes.byref(out)) == hb.H2O_EINVAL
+    assert lib.h2o_cache_init(ctypes.byref(ok), None, 1 << 20, None, ctypes.byref(out)) == hb.H2O_EINVAL
+    assert lib.h2o_cache_init(ctypes.byref(ok), 0x1008, 1 << 20, None, ctypes.byref(out)) == hb.H2O_EINVAL
+    assert lib.h2o_cache_init(ctypes.byref(ok), 0x1000, 16, None, ctypes.byref(out)) == hb.H2O_ENOMEM
+    odd = hb.make_config(1, 1, 80, 4, 4, hb.H2O_F16)
+    assert lib.h2o_cache_init(ctypes.byref(odd), 0x1000, 1 << 20, None, ctypes.byref(out)) == hb.H2O_EUNSUPPORTED
+    assert out.value is None
+    assert lib.h2o_decode_step(None, 0x1000, 0x1000, 0x1000, 0x1000, None) == hb.H2O_EINVAL
+    assert lib.h2o_cache_reset(None, None) == hb.H2O_EINVAL
+    assert lib.h2o_cache_tokens_seen(None) == hb.H2O_EINVAL
+    assert lib.h2o_prefill_colsum(ctypes.byref(ok), None, 0x1000, 8, 0x1000, 1 << 20, 0x1000, None) == hb.H2O_EINVAL
+    assert lib.h2o_prefill_colsum(ctypes.byref(ok), 0x1000, 0x1000, 8, 0x1000, 8, 0x1000, None) == hb.H2O_ENOMEM
+    assert lib.h2o_prefill_colsum(ctypes.byref(ok), 0x1000, 0x1000, hb.H2O_MAX_PROMPT + 1, 0x1000,
+                                  1 << 30, 0x1000, None) == hb.H2O_EUNSUPPORTED
+    lib.h2o_cache_destroy(None)
+    assert hb.h2o_status_str(0) == "ok"
+    assert "unsupported" in hb.h2o_status_str(hb.H2O_EUNSUPPORTED)
+    assert hb.h2o_status_str(-99) == "unknown status"
+
+
+def test_synthetic_inputs_are_seeded_and_shaped():
+    import torch
+    from paper_2306_14048_amd import synth
+    w = synth.WORKLOADS
+    assert (w["opt6.7b_layer_f16"].heavy, w["opt6.7b_layer_f16"].recent) == (205, 205)
+    assert (w["opt30b_layer_f16"].heavy, w["opt30b_layer_f16"].recent) == (103, 102)
+    assert (w["stack32_f16"].heavy, w["stack32_f16"].recent) == (205, 205)
+    assert (w["prefill_bf16"].heavy, w["prefill_bf16"].recent) == (410, 409)
+    a = synth.make_prompt(2, 3, 16, 8, torch.float16, 1.0, "cpu", seed=5)
+    b = synth.make_prompt(2, 3, 16, 8, torch.float16, 1.0, "cpu", seed=5)
+    c = synth.make_prompt(2, 3, 16, 8, torch.float16, 1.0, "cpu", seed=6)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    assert not torch.equal(a[1], c[1])
+    q, k, v = synth.make_steps(2, 3, 8, 5, torch.bfloat16, 1.0, "cpu", seed=5)
+    assert q.shape == (5, 2, 3, 8) and k.dtype == torch.bfloat16
+    # heavy-tailed keys: per-token norms spread over more than a decade at sigma = 1
+    K = synth.make_prompt(1, 1, 4096, 64, torch.float32, 1.0, "cpu", seed=1)[1]
+    norms = K[0, 0].norm(dim=-1)
+    assert norms.max() / norms.median() > 8

@@ -1,0 +1,143 @@
+"""GPU parity of h2o_decode_step against the CPU oracle, through the C ABI.
+
+Every case starts both sides from the same cache state: the oracle runs the
+prompt phase (fp64, scores rounded to binary32 when stored), its resident
+tokens are loaded into the device cache with h2o_cache_restore, then T steps run
+on the device and are compared step by step (kept-position sets exactly, outputs
+within the dtype's tolerance, final scores).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.h2o_oracle import OracleHead, map_heads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sample=None,
+             permute_slots=False):
+    from paper_2306_14048_amd import binding as hb, synth
+    dev = torch.device("cuda:0")
+    k = heavy + recent
+    scale_d = parity.oracle_scale(d, scale)
+    heads = [(b, h) for b in range(B) for h in range(Hh)]
+    if sample is not None and sample < len(heads):
+        rng = np.random.default_rng(seed)
+        heads = [heads[i] for i in sorted(rng.choice(len(heads), sample, replace=False))]
+    qs, ks, vs = synth.make_steps(B, Hh, d, T, dtype, sigma, dev, seed)
+    cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, scale, device=dev)
+    all_heads = [(b, h) for b in range(B) for h in range(Hh)]
+    if n > 0:
+        Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, sigma, dev, seed)
+        Qh, Kh, Vh = Q.cpu(), K.cpu(), V.cpu()
+        oracles, _ = parity.oracle_prefill_heads(Qh, Kh, Vh, all_heads, heavy, recent, scale_d,
+                                                 cap=n + T)
+        Kc, Vc, acc, pos = parity.cache_state_from_oracles(oracles, B, Hh, k, Kh, Vh)
+        if permute_slots:
+            # occupied slots stay a prefix, their order inside it is shuffled per head
+            g = torch.Generator().manual_seed(seed)
+            c = min(n, k)
+            for b, h in all_heads:
+                perm = torch.randperm(c, generator=g)
+                Kc[b, h, :c] = Kc[b, h, perm]; Vc[b, h, :c] = Vc[b, h, perm]
+                acc[b, h, :c] = acc[b, h, perm]; pos[b, h, :c] = pos[b, h, perm]
+        cache.restore(Kc.to(dev), Vc.to(dev), acc.to(dev), pos.to(dev), n)
+    else:
+        oracles = {bh: OracleHead(d, heavy, recent, scale_d, score_f32=True, cap=T) for bh in all_heads}
+    outs, snaps = parity.run_gpu_decode(cache, qs, ks, vs)
+    pos_f, acc_f = cache.snapshot()
+    torch.cuda.synchronize()
+    pos_f, acc_f = pos_f.cpu(), acc_f.cpu()
+    assert cache.tokens_seen == n + T
+    qh, kh, vh = qs.cpu(), ks.cpu(), vs.cpu()
+    tol = parity.OUT_TOL[dtype]
+
+    def one(bh):
+        b, h = bh
+        st = parity.check_head_decode(oracles[bh], qh[:, b, h], kh[:, b, h], vh[:, b, h],
+                                      outs[:, b, h], snaps[:, b, h], recent, tol)
+        parity.check_final_scores(oracles[bh], pos_f[b, h], acc_f[b, h], st)
+        return st
+
+    results, _ = map_heads(one, heads)
+    total = parity.DecodeStats()
+    for st in results:
+        total.merge(st)
+    print("\n[decode parity] B=%d Hh=%d d=%d n=%d T=%d H=%d R=%d %s: head-steps %d, near-tied %d, "
+          "excused %d, max out l2 %.2e linf %.2e, scores not bit-equal %d (max rel %.1e)"
+          % (B, Hh, d, n, T, heavy, recent, str(dtype).split(".")[-1], total.head_steps,
+             total.near_tied_steps, total.excused, total.max_out_l2, total.max_out_linf,
+             total.score_mismatch, total.max_score_rel), flush=True)
+    assert total.excused <= max(1, int(0.001 * total.head_steps)) or total.excused == 0
+    assert total.max_score_rel <= 1e-6
+    cache.close()
+    return total
+
+
+def test_tiny_f32_config_full():
+    """Workload 1: batch 1, 8 heads, d 64, prompt 256, 64 steps, budget 32 + 32, fp32."""
+    from paper_2306_14048_amd import synth
+    w = synth.WORKLOADS["tiny_f32"]
+    run_case(w.batch, w.heads, w.head_dim, w.prompt, w.steps, w.heavy, w.recent, w.dtype, w.sigma,
+             synth.BASE_SEED)
+
+
+@pytest.mark.parametrize("dt,d", [("f16", 128), ("bf16", 128), ("f32", 128), ("f16", 64),
+                                  ("bf16", 64), ("f32", 64)])
+@pytest.mark.parametrize("n,T,heavy,recent", [
+    (96, 40, 13, 10),      # ragged budget, several rounds, 4-wave kernel
+    (300, 30, 103, 102),   # the OPT-30B-shaped budget (205 slots)
+    (600, 24, 205, 205),   # the OPT-6.7B-shaped budget (410 slots): 8-wave kernel, ring = all rounds
+])
+def test_decode_dtypes_and_budgets(dt, d, n, T, heavy, recent):
+    run_case(2, 3, d, n, T, heavy, recent, torch_dt[dt], 1.0, 11)
+
+
+@pytest.mark.parametrize("heavy,recent,n,T", [
+    (300, 333, 700, 20),     # 633 slots: ring shorter than the stream (refills mid-stream)
+    (1500, 611, 2200, 6),    # 2111 slots: more than two bookkeeping entries per thread
+    (2048, 2048, 4200, 3),   # the largest budget (needs the raised LDS limit)
+    (1, 0, 9, 12), (0, 1, 9, 12), (1, 1, 3, 12), (4, 3, 7, 9),   # smallest budgets
+])
+def test_decode_budget_extremes(heavy, recent, n, T):
+    run_case(1, 2, 128, n, T, heavy, recent, torch.float16, 1.0, 5)
+
+
+@pytest.mark.parametrize("heavy,recent", [(16, 16), (0, 24), (24, 0), (7, 1)])
+def test_decode_from_empty_cache(heavy, recent):
+    """No prompt: the cache fills slot by slot, then eviction starts (Algorithm 1's
+    `i <= k` branch); recent = 0 lets the new token itself lose; heavy = 0 is a
+    sliding window."""
+    run_case(2, 2, 64, 0, 70, heavy, recent, torch.float16, 0.75, 3)
+
+
+def test_decode_short_prompt_then_fill():
+    """Prompt shorter than the budget: everything is kept, then slots fill up."""
+    run_case(1, 4, 128, 20, 60, 24, 24, torch.bfloat16, 1.0, 9)
+
+
+def test_decode_explicit_scale():
+    run_case(1, 2, 64, 64, 16, 8, 8, torch.float32, 0.75, 21, scale=0.2)
+
+
+def test_slot_order_does_not_matter():
+    """Which slot holds which token is not observable: shuffling the slots of the
+    starting state must give the same kept positions and outputs."""
+    a = run_case(1, 4, 128, 256, 32, 40, 24, torch.float16, 1.0, 17)
+    b = run_case(1, 4, 128, 256, 32, 40, 24, torch.float16, 1.0, 17, permute_slots=True)
+    assert a.excused == b.excused == 0
+
+
+def test_opt67b_layer_config_all_heads():
+    """Workload 2 at full size, the launch configuration the benchmark times:
+    batch 16 x 32 heads, d 128, prompt 2048, 256 steps, budget 205 + 205, fp16.
+    Every head is checked on every step."""
+    from paper_2306_14048_amd import synth
+    w = synth.WORKLOADS["opt6.7b_layer_f16"]
+    st = run_case(w.batch, w.heads, w.head_dim, w.prompt, w.steps, w.heavy, w.recent, w.dtype,
+                  w.sigma, synth.BASE_SEED)
+    assert st.head_steps == w.batch * w.heads * w.steps
