@@ -8,7 +8,10 @@ Rules applied (stated in the design notes):
     lowest candidate score; the oracle then adopts the device's choice
     (resync) and the step is counted.  Anything else fails.
   * outputs: ||o_gpu - o_ref||_2 / ||o_ref||_2 and max|diff| / max|o_ref| both
-    within `out_tol` (1e-5 fp32, 2e-3 fp16/bf16).
+    within `out_tol` (1e-5 fp32, 2e-3 fp16/bf16) plus, for bf16 only, 2^-8: the
+    device stores its fp32 result in the output dtype with one rounding, and a
+    bf16 value (8 significand bits) is off by up to 2^-8 relative from that
+    rounding alone, which no kernel can avoid (fp16: 2^-11, inside the tolerance).
 Nothing the oracle consumes or is compared against ever comes from the device
 except the device's own results under test.
 """
@@ -23,6 +26,9 @@ from oracle.h2o_oracle import OracleHead, map_heads
 
 NEAR_TIE = 1e-6
 OUT_TOL = {torch.float32: 1e-5, torch.float16: 2e-3, torch.bfloat16: 2e-3}
+# allowance for storing the fp32 result in the output dtype: only bf16's rounding
+# step is coarser than the tolerance itself
+OUT_STORE_SLACK = {torch.float32: 0.0, torch.float16: 0.0, torch.bfloat16: 2.0 ** -8}
 
 
 def oracle_scale(d: int, scale: float = 0.0) -> float:
@@ -115,6 +121,7 @@ def run_gpu_decode(cache, qs, ks, vs, snapshot_heads=None):
 
 
 def check_head_decode(o: OracleHead, qs, ks, vs, outs, snaps, recent, out_tol) -> DecodeStats:
+    out_tol = out_tol + OUT_STORE_SLACK[outs.dtype]
     """Steps one oracle head through T steps and compares with the device's
     per-step outputs [T, d] and slot tables [T, k] of the same head."""
     st = DecodeStats()
