@@ -117,23 +117,255 @@ __device__ inline unsigned long long wave_min(unsigned long long v)
 }
 constexpr unsigned long long NO_CANDIDATE = ~0ull;
 
+// ---- pieces shared by the two kernels -------------------------------------------
+
+// Adds this lane's fp32 partial output (EPL columns of row group `sub`) into the
+// workgroup's output row, multiplies nothing: o_l[wave][column] gets the wave's sum.
+template <int EPL, int LPR, int D>
+__device__ inline void wave_output_to_lds(float (&o)[EPL], float *o_l, int wave, int sub, int li)
+{
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) o[i] += __shfl_xor(o[i], m, 64);
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) o_l[wave * D + li * EPL + i] = o[i];
+    }
+}
+
+// Final writes of a step: the output row, and the new token into slot `target`
+// (K row, V row, first score, position); target < 0 = the token is not kept.
+template <int DT, int D, int NW>
+__device__ inline void write_back(const float *o_l, float p_self, int target, int t, size_t hoff,
+                                  int head, char *Kb, char *Vb, float *acc_g, int32_t *pos_g,
+                                  const typename Elem<DT>::T *knh, const typename Elem<DT>::T *vnh,
+                                  char *out_g)
+{
+    using E = Elem<DT>;
+    using T = typename E::T;
+    constexpr int EPL = E::EPL, LPR = D / EPL;
+    constexpr unsigned ROWB = D * sizeof(T);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < D) {
+        float r = p_self * E::to_f(vnh[tid]);
+#pragma unroll
+        for (int w = 0; w < NW; ++w) r += o_l[w * D + tid];
+        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r);
+    }
+    if (target >= 0) {
+        if (tid == 0) { pos_g[hoff + target] = t; acc_g[hoff + target] = p_self; }
+        if (wave == NW - 1) {            // a wave that is not busy with the output row
+            if (lane < LPR) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(knh + lane * EPL);
+                *reinterpret_cast<uint4 *>(Kb + (size_t)target * ROWB + lane * 16) = v;
+            } else if (lane < 2 * LPR) {
+                const int l2 = lane - LPR;
+                const uint4 v = *reinterpret_cast<const uint4 *>(vnh + l2 * EPL);
+                *reinterpret_cast<uint4 *>(Vb + (size_t)target * ROWB + l2 * 16) = v;
+            }
+        }
+    }
+}
+
+// ---- register-resident kernel: every row of the head fits the ring -----------------
+//
+// Requires n_occ <= U * RPI (<= one slot per thread).  Straight-line code: the U
+// key loads of a wave go out first, each buffer is refilled with the matching
+// value row as soon as it has been used, and no load is conditional, so the
+// compiler can wait for exactly the load it needs (vector loads complete in issue
+// order; a load behind a branch would make every later wait conservative).
+// Rounds past the occupied slots re-read the last occupied row and are ignored.
+// The lanes' fp64 partial dot products go to LDS ([row][lane], padded pitch) and
+// thread j adds up row j, so the logit of slot j, its probability, score and
+// position all live in registers of thread j.
 template <int DT, int D, int NW, int U>
-__global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
+__global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
     char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale)
 {
-    // k: slots per head (stride); n_occ: occupied slots, always the prefix
-    // [0, n_occ) of the head's slots (slots fill in index order and are only
-    // ever overwritten in place); t: position of the token being generated.
     using E = Elem<DT>;
     using T = typename E::T;
     constexpr int EPL = E::EPL;          // elements per lane per 16-byte load
     constexpr int LPR = D / EPL;         // lanes per row
     constexpr int RPW = 64 / LPR;        // rows per wave per load
-    constexpr int NT = NW * 64;
     constexpr int RPI = NW * RPW;        // rows per workgroup-wide round
+    constexpr int ROWS = U * RPI;        // rows the ring covers (<= threads)
+    constexpr int PITCH = LPR + 1;       // doubles per row of partials (bank spread)
+    constexpr unsigned ROWB = D * sizeof(T);
+    static_assert(LPR >= 8 && LPR <= 32, "a row is read by 8, 16 or 32 lanes");
+    static_assert(ROWS <= NW * 64, "one slot per thread");
+
+    const int head = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane / LPR, li = lane % LPR;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *part_l = reinterpret_cast<double *>(smem);                 // [ROWS][PITCH]
+    double *red_max = part_l + ROWS * PITCH;                           // [NW]
+    double *red_sum = red_max + NW;                                    // [NW]
+    unsigned long long *red_key = reinterpret_cast<unsigned long long *>(red_sum + NW);
+    float *p_l = reinterpret_cast<float *>(red_key + NW);              // [ROWS]
+    float *o_l = p_l + ROWS;                                           // [NW][D]
+    int *target_l = reinterpret_cast<int *>(o_l + NW * D);             // [1]
+
+    const size_t hoff = (size_t)head * k;
+    char *Kb = Kc + hoff * ROWB;                                       // uniform bases
+    char *Vb = Vc + hoff * ROWB;
+    const T *qh = reinterpret_cast<const T *>(q_g) + (size_t)head * D;
+    const T *knh = reinterpret_cast<const T *>(kn_g) + (size_t)head * D;
+    const T *vnh = reinterpret_cast<const T *>(vn_g) + (size_t)head * D;
+
+    const int row0 = wave * RPW + sub;   // this lane's row inside a round
+    const int last = max(n_occ, 1) - 1;  // clamp target: slot 0 exists even when empty
+
+    // q and the new key first: whatever the first arithmetic needs must be
+    // requested before the long key stream
+    const uint4 qraw = *reinterpret_cast<const uint4 *>(qh + li * EPL);
+    const uint4 kraw = *reinterpret_cast<const uint4 *>(knh + li * EPL);
+    unsigned off[U];
+    uint4 buf[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        off[u] = (unsigned)min(u * RPI + row0, last) * ROWB + (unsigned)li * 16u;
+        buf[u] = *reinterpret_cast<const uint4 *>(Kb + off[u]);
+    }
+    // slot `tid`'s bookkeeping (unconditional, clamped: a conditional load would
+    // be merged with its default right here and stall on the whole stream)
+    const int pos_j = pos_g[hoff + min(tid, last)];
+    float acc_j = acc_g[hoff + min(tid, last)];
+    __builtin_amdgcn_sched_barrier(0);   // every request above leaves before any arithmetic
+
+    // this lane's slice of q (widened exactly) and the token's own logit
+    double qd[EPL];
+    double s_self;
+    {
+        const T *qe = reinterpret_cast<const T *>(&qraw);
+        const T *ke = reinterpret_cast<const T *>(&kraw);
+        double a = 0.0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            qd[i] = (double)E::to_f(qe[i]);
+            a = fma((double)E::to_f(ke[i]), qd[i], a);
+        }
+        s_self = group_sum<LPR>(a) * scale;
+    }
+
+    // ---- logits: one pass over the cached keys --------------------------------
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const T *x = reinterpret_cast<const T *>(&buf[u]);
+        double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+        for (int i = 0; i < EPL; i += 2) {
+            a0 = fma((double)E::to_f(x[i]), qd[i], a0);
+            a1 = fma((double)E::to_f(x[i + 1]), qd[i + 1], a1);
+        }
+        buf[u] = *reinterpret_cast<const uint4 *>(Vb + off[u]);   // value row takes the buffer
+        part_l[(u * RPI + row0) * PITCH + li] = a0 + a1;
+        __builtin_amdgcn_sched_barrier(0);   // one row at a time: bounds live registers
+    }
+    lds_barrier();
+
+    // ---- exact softmax over the occupied slots + the token itself -------------
+    const bool mine = tid < n_occ;       // thread j owns slot j
+    double s_j = -INFINITY;
+    if (mine) {
+        const double *pr = part_l + tid * PITCH;
+        double a = pr[0];
+#pragma unroll
+        for (int c = 1; c < LPR; ++c) a += pr[c];
+        s_j = a * scale;
+    }
+    {
+        const double mw = wave_max(s_j);
+        if (lane == 0) red_max[wave] = mw;
+    }
+    lds_barrier();
+    double mx = s_self;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) mx = fmax(mx, red_max[w]);
+    const double e_j = mine ? exp(s_j - mx) : 0.0;
+    const double e_self = exp(s_self - mx);
+    {
+        const double dw = wave_sum(e_j);
+        if (lane == 0) red_sum[wave] = dw;
+    }
+    lds_barrier();
+    double den = e_self;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) den += red_sum[w];
+    const float p_self = (float)(e_self / den);
+    const float p_j = (float)(e_j / den);
+
+    // ---- score update and eviction candidate ----------------------------------
+    acc_j += p_j;                                            // binary32 accumulate
+    if (tid < ROWS) p_l[tid] = p_j;                          // 0 for unoccupied rows
+    unsigned long long key = NO_CANDIDATE;
+    if (mine && pos_j <= t - recent)                         // window after this step = {t-R+1..t}
+        key = ((unsigned long long)__float_as_uint(acc_j) << 32) | (unsigned)pos_j;
+    {
+        const unsigned long long kw = wave_min(key);
+        if (lane == 0) red_key[wave] = kw;
+        if (tid == 0) *target_l = n_occ < k ? n_occ : -1;    // a free slot, if any
+    }
+    lds_barrier();
+    if (n_occ >= k) {
+        // evict the smallest (score, position); with recent == 0 the token itself
+        // competes with its first score and may lose (target stays -1)
+        unsigned long long win = red_key[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) win = umin64(win, red_key[w]);
+        const unsigned long long self_key =
+            ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
+        if (key == win && key != NO_CANDIDATE && (recent != 0 || win < self_key))
+            *target_l = tid;                                 // keys are unique (positions are)
+    }
+
+    // ---- output: one pass over the cached values ------------------------------
+    float o[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float p = p_l[u * RPI + row0];
+        const T *x = reinterpret_cast<const T *>(&buf[u]);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, E::to_f(x[i]), o[i]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    wave_output_to_lds<EPL, LPR, D>(o, o_l, wave, sub, li);
+    lds_barrier();
+
+    // ---- write-back -----------------------------------------------------------
+    const int target = *target_l;
+    if (mine && tid != target) acc_g[hoff + tid] = acc_j;
+    write_back<DT, D, NW>(o_l, p_self, target, t, hoff, head, Kb, Vb, acc_g, pos_g, knh, vnh, out_g);
+}
+
+// ---- streaming kernel: any budget up to H2O_MAX_BUDGET --------------------------------
+//
+// The key rounds followed by the value rounds form one stream pulled through a
+// ring of U register buffers per wave: a buffer is refilled with the entry U
+// places ahead as soon as it has been consumed.  Logits, probabilities and the
+// per-slot bookkeeping live in LDS; thread j % NT handles slot j.
+template <int DT, int D, int NW, int U>
+__global__ __launch_bounds__(NW * 64, 4) void decode_stream_kernel(
+    char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
+    int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
+    const char *__restrict__ kn_g, const char *__restrict__ vn_g,
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale)
+{
+    using E = Elem<DT>;
+    using T = typename E::T;
+    constexpr int EPL = E::EPL;
+    constexpr int LPR = D / EPL;
+    constexpr int RPW = 64 / LPR;
+    constexpr int NT = NW * 64;
+    constexpr int RPI = NW * RPW;
     constexpr unsigned ROWB = D * sizeof(T);
     static_assert(LPR >= 8 && LPR <= 32, "a row is read by 8, 16 or 32 lanes");
 
@@ -154,45 +386,32 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
     int *target_l = reinterpret_cast<int *>(red_key + NW);     // [1]
 
     const size_t hoff = (size_t)head * k;
-    const char *Kb = Kc + hoff * ROWB;                         // uniform bases
-    const char *Vb = Vc + hoff * ROWB;
+    char *Kb = Kc + hoff * ROWB;
+    char *Vb = Vc + hoff * ROWB;
     const T *qh = reinterpret_cast<const T *>(q_g) + (size_t)head * D;
     const T *knh = reinterpret_cast<const T *>(kn_g) + (size_t)head * D;
     const T *vnh = reinterpret_cast<const T *>(vn_g) + (size_t)head * D;
 
     const int rounds = (n_occ + RPI - 1) / RPI;
-    const int row0 = wave * RPW + sub;   // this lane's row inside a round
+    const int row0 = wave * RPW + sub;
     const int vbase = (rounds + U - 1) / U * U;   // stream index of value round 0
     // stream entry e: key round e for e < rounds, value round e - vbase for
     // vbase <= e < vbase + rounds, nothing in between; entry e lives in buf[e % U]
     auto load_row = [&](const char *base, int round) -> uint4 {
-        const unsigned rc = (unsigned)min(round * RPI + row0, n_occ - 1);   // clamp: stays in bounds
+        const unsigned rc = (unsigned)min(round * RPI + row0, max(n_occ, 1) - 1);   // in bounds
         return *reinterpret_cast<const uint4 *>(base + (rc * ROWB + (unsigned)li * 16u));
     };
 
+    const uint4 qraw = *reinterpret_cast<const uint4 *>(qh + li * EPL);
+    const uint4 kraw = *reinterpret_cast<const uint4 *>(knh + li * EPL);
     uint4 buf[U];
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (u < rounds) buf[u] = load_row(Kb, u);
 
-    // this thread's share of the slot bookkeeping (slots tid, tid + NT, ...):
-    // the first JR entries are requested now, behind the key stream
-    constexpr int JR = 2;
-    int pos_r[JR];
-    float acc_r[JR];
-#pragma unroll
-    for (int i = 0; i < JR; ++i) {
-        const int j = tid + i * NT;
-        pos_r[i] = j < n_occ ? pos_g[hoff + j] : -1;
-        acc_r[i] = j < n_occ ? acc_g[hoff + j] : 0.f;
-    }
-
-    // this lane's slice of q (widened exactly) and the token's own logit
     double qd[EPL];
     double s_self;
     {
-        const uint4 qraw = *reinterpret_cast<const uint4 *>(qh + li * EPL);
-        const uint4 kraw = *reinterpret_cast<const uint4 *>(knh + li * EPL);
         const T *qe = reinterpret_cast<const T *>(&qraw);
         const T *ke = reinterpret_cast<const T *>(&kraw);
         double a = 0.0;
@@ -204,9 +423,8 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
         s_self = group_sum<LPR>(a) * scale;
     }
 
-    // ---- logits: one pass over the cached keys --------------------------------
-    // m_run: running maximum of this lane group's logits (the softmax shift)
-    double m_run = s_self;
+    // ---- logits ---------------------------------------------------------------
+    double m_run = s_self;               // running maximum (the softmax shift)
     for (int r = 0; r < rounds; r += U) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -224,7 +442,7 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
                 if (li == 0 && row < n_occ) s_l[row] = a;
                 m_run = fmax(m_run, a);          // clamped duplicates repeat a real row
             }
-            __builtin_amdgcn_sched_barrier(0);   // one row at a time: bounds live registers
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     {
@@ -239,24 +457,17 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
         const double mw = wave_max(m_run);
         if (lane == 0) red_max[wave] = mw;
     }
-#pragma unroll
-    for (int i = 0; i < JR; ++i) {
-        const int j = tid + i * NT;
-        if (j < n_occ) { pos_l[j] = pos_r[i]; acc_l[j] = acc_r[i]; }
-    }
-    for (int j = tid + JR * NT; j < n_occ; j += NT) {
+    for (int j = tid; j < n_occ; j += NT) {
         pos_l[j] = pos_g[hoff + j];
         acc_l[j] = acc_g[hoff + j];
     }
     lds_barrier();
 
-    // ---- exact softmax over the occupied slots + the token itself -------------
-    // (slot j's bookkeeping is always handled by thread j % NT, so pos_l / acc_l
-    // entries are only ever touched by the thread that wrote them)
+    // ---- exact softmax (slot j is always handled by thread j % NT, so pos_l /
+    // acc_l entries are only ever touched by the thread that wrote them) --------
     double mx = red_max[0];
 #pragma unroll
     for (int w = 1; w < NW; ++w) mx = fmax(mx, red_max[w]);
-
     double d_loc = 0.0;
     for (int j = tid; j < n_occ; j += NT) {
         const double e = exp(s_l[j] - mx);
@@ -274,7 +485,7 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
     for (int w = 0; w < NW; ++w) den += red_sum[w];
     const float p_self = (float)(e_self / den);
 
-    // ---- probabilities, score update, eviction candidates ---------------------
+    // ---- score update and eviction candidates ---------------------------------
     unsigned long long key = NO_CANDIDATE;
     const int last_cand = t - recent;    // window after this step = {t-R+1 .. t}
     for (int j = tid; j < n_occ; j += NT) {
@@ -292,23 +503,20 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
         if (tid == 0) *target_l = n_occ < k ? n_occ : -1;
     }
     lds_barrier();
-    key = red_key[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) key = umin64(key, red_key[w]);
-    // Which slot receives the new token: the first free one if any; else the
-    // evicted one.  With recent == 0 the token itself competes with its first
-    // score and may lose, in which case nothing is written (target stays -1).
     if (n_occ >= k) {
+        key = red_key[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) key = umin64(key, red_key[w]);
         const unsigned long long self_key =
             ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
-        if (recent != 0 || key < self_key) {
+        if (key != NO_CANDIDATE && (recent != 0 || key < self_key)) {
             const int wpos = (int)(unsigned)(key & 0xffffffffu);
             for (int j = tid; j < n_occ; j += NT)
                 if (pos_l[j] == wpos) *target_l = j;      // positions are unique
         }
     }
 
-    // ---- output: one pass over the cached values ------------------------------
+    // ---- output ---------------------------------------------------------------
     float o[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) o[i] = 0.f;
@@ -329,66 +537,61 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_kernel(
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-#pragma unroll
-    for (int m = LPR; m < 64; m <<= 1) {
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) o[i] += __shfl_xor(o[i], m, 64);
-    }
-    if (sub == 0) {
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) o_l[wave * D + li * EPL + i] = o[i];
-    }
+    wave_output_to_lds<EPL, LPR, D>(o, o_l, wave, sub, li);
     lds_barrier();
 
-    // ---- write-back: output, scores, and the new token into its slot ----------
+    // ---- write-back -----------------------------------------------------------
     const int target = *target_l;
-    if (tid < D) {
-        float r = p_self * E::to_f(vnh[tid]);
-#pragma unroll
-        for (int w = 0; w < NW; ++w) r += o_l[w * D + tid];
-        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r);
-    }
     for (int j = tid; j < n_occ; j += NT)
         if (j != target) acc_g[hoff + j] = acc_l[j];
-    if (target >= 0 && tid == 0) acc_g[hoff + target] = p_self;
-    if (target >= 0) {
-        if (tid == 0) pos_g[hoff + target] = t;
-        if (wave == NW - 1) {            // a wave that is not busy with the output row
-            if (lane < LPR) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(knh + lane * EPL);
-                *reinterpret_cast<uint4 *>(const_cast<char *>(Kb) + (size_t)target * ROWB + lane * 16) = v;
-            } else if (lane < 2 * LPR) {
-                const int l2 = lane - LPR;
-                const uint4 v = *reinterpret_cast<const uint4 *>(vnh + l2 * EPL);
-                *reinterpret_cast<uint4 *>(const_cast<char *>(Vb) + (size_t)target * ROWB + l2 * 16) = v;
-            }
-        }
+    write_back<DT, D, NW>(o_l, p_self, target, t, hoff, head, Kb, Vb, acc_g, pos_g, knh, vnh, out_g);
+}
+
+inline hipError_t raise_lds_limit(const void *kern, size_t smem, bool &raised)
+{
+    if (smem > 48 * 1024 && !raised) {
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           150 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
     }
+    return hipSuccess;
+}
+
+#define H2O_DECODE_ARGS                                                                         \
+    c.K, c.V, c.acc, c.pos, static_cast<const char *>(q), static_cast<const char *>(kn),        \
+        static_cast<const char *>(vn), static_cast<char *>(out), c.k, (c.t < c.k ? c.t : c.k),  \
+        c.t, c.cfg.recent, c.scale
+
+template <int DT, int D, int NW, int U>
+hipError_t launch_resident(const h2o_cache &c, const void *q, const void *kn, const void *vn,
+                           void *out, hipStream_t st)
+{
+    constexpr int LPR = D / Elem<DT>::EPL;
+    constexpr int ROWS = U * NW * (64 / LPR);
+    constexpr size_t smem = (size_t)ROWS * (LPR + 1) * 8 + (size_t)NW * 24 + (size_t)ROWS * 4 +
+                            (size_t)NW * D * 4 + 16;
+    auto kern = decode_resident_kernel<DT, D, NW, U>;
+    static bool raised = false;
+    hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st,
+                       H2O_DECODE_ARGS);
+    return hipGetLastError();
 }
 
 template <int DT, int D, int NW, int U>
-hipError_t launch(const h2o_cache &c, const void *q, const void *kn, const void *vn, void *out,
-                  hipStream_t st)
+hipError_t launch_stream(const h2o_cache &c, const void *q, const void *kn, const void *vn,
+                         void *out, hipStream_t st)
 {
-    const int k = c.k;
-    const int kp = (k + 2) & ~1;
-    const size_t smem = (size_t)kp * 20 + (size_t)NW * D * 4 + (size_t)NW * 28 + 16;
-    auto kern = decode_kernel<DT, D, NW, U>;
-    if (smem > 48 * 1024) {
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               150 * 1024);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
-    }
-    const int heads = c.cfg.batch * c.cfg.heads;
-    hipLaunchKernelGGL(kern, dim3(heads), dim3(NW * 64), smem, st, c.K, c.V, c.acc, c.pos,
-                       static_cast<const char *>(q), static_cast<const char *>(kn),
-                       static_cast<const char *>(vn), static_cast<char *>(out), k,
-                       c.t < k ? c.t : k, c.t, c.cfg.recent, c.scale);
+    const int kp = (c.k + 2) & ~1;
+    const size_t smem = (size_t)kp * 20 + (size_t)NW * D * 4 + (size_t)NW * 24 + 16;
+    auto kern = decode_stream_kernel<DT, D, NW, U>;
+    static bool raised = false;
+    hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st,
+                       H2O_DECODE_ARGS);
     return hipGetLastError();
 }
 
@@ -396,21 +599,27 @@ template <int DT, int D>
 hipError_t pick(const h2o_cache &c, const void *q, const void *kn, const void *vn, void *out,
                 hipStream_t st)
 {
-    // Waves per head and ring depth follow the budget: the ring should hold all
-    // key rounds when it can (then every value row is requested before the
-    // softmax), and small budgets use 4 waves so more heads share a CU.
+    // Waves per head and ring depth follow the number of occupied slots: while
+    // every row fits the ring (at most UMAX rounds, and at most one slot per
+    // thread) the head is register-resident, with 4 waves per head for small
+    // budgets so that more heads share a CU, else 8; beyond that the 8-wave
+    // kernel streams the rows through a 13-deep ring.
     constexpr int LPR = D / Elem<DT>::EPL;
     constexpr int RPW = 64 / LPR;
-    const int k = c.t < c.k ? c.t : c.k;      // occupied slots
-    if (k <= 4 * RPW * 13) {
-        const int rounds = (k + 4 * RPW - 1) / (4 * RPW);
-        if (rounds <= 4) return launch<DT, D, 4, 4>(c, q, kn, vn, out, st);
-        if (rounds <= 8) return launch<DT, D, 4, 8>(c, q, kn, vn, out, st);
-        return launch<DT, D, 4, 13>(c, q, kn, vn, out, st);
+    constexpr int UMAX = RPW * 13 <= 64 ? 13 : 8;
+    const int occ = c.t < c.k ? c.t : c.k;
+    if (occ <= 4 * RPW * UMAX) {
+        const int rounds = (occ + 4 * RPW - 1) / (4 * RPW);
+        if (rounds <= 4) return launch_resident<DT, D, 4, 4>(c, q, kn, vn, out, st);
+        if (rounds <= 8) return launch_resident<DT, D, 4, 8>(c, q, kn, vn, out, st);
+        if constexpr (UMAX > 8) return launch_resident<DT, D, 4, 13>(c, q, kn, vn, out, st);
     }
-    const int rounds = (k + 8 * RPW - 1) / (8 * RPW);
-    if (rounds <= 8) return launch<DT, D, 8, 8>(c, q, kn, vn, out, st);
-    return launch<DT, D, 8, 13>(c, q, kn, vn, out, st);
+    const int rounds = (occ + 8 * RPW - 1) / (8 * RPW);
+    if (rounds <= 8) return launch_resident<DT, D, 8, 8>(c, q, kn, vn, out, st);
+    if constexpr (UMAX > 8) {
+        if (rounds <= 13) return launch_resident<DT, D, 8, 13>(c, q, kn, vn, out, st);
+    }
+    return launch_stream<DT, D, 8, 13>(c, q, kn, vn, out, st);
 }
 
 }  // namespace
