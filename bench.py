@@ -73,7 +73,10 @@ def main():
     ap.add_argument("--workload", default="opt6.7b_layer_f16")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-heads", type=int, default=64)
+    ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = all)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (calibrates the profiler's "
+                         "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (heads are independent and would "
@@ -193,8 +196,16 @@ def main():
         "decode_tokens_per_s": B / (dec_us * 1e-6),
         "prefill_ms": min(prefill_ms),
     }
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)                       # the dispatch to read: 256 MiB in, 256 MiB out
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(w, args.cpu_heads)
+        heads_total = B * Hh
+        rec["cpu_baseline"] = cpu_baseline(w, args.cpu_heads if args.cpu_heads > 0 else heads_total)
     print(json.dumps(rec))
     cache.close()
 

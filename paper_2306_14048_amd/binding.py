@@ -191,10 +191,14 @@ class H2OCache:
 
     def close(self):
         if getattr(self, "handle", None):
-            h2o_cache_destroy(self.handle)
+            _lib.h2o_cache_destroy(self.handle)
             self.handle = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: module globals may be gone
+            pass
 
     @property
     def shape_heads(self):

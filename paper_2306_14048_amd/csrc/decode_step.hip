@@ -104,6 +104,14 @@ __device__ inline double wave_max(double v)
     v = row_max(v);
     return fmax(fmax(lane_value(v, 0), lane_value(v, 16)), fmax(lane_value(v, 32), lane_value(v, 48)));
 }
+__device__ inline double wave_min_f64(double v)   // NaN entries are ignored
+{
+    v = fmin(v, dpp<DPP_XOR1>(v));
+    v = fmin(v, dpp<DPP_XOR2>(v));
+    v = fmin(v, dpp<DPP_HALF_MIRROR>(v));
+    v = fmin(v, dpp<DPP_MIRROR>(v));
+    return fmin(fmin(lane_value(v, 0), lane_value(v, 16)), fmin(lane_value(v, 32), lane_value(v, 48)));
+}
 __device__ inline double wave_sum(double v)
 {
     v = group_sum<16>(v);
@@ -171,15 +179,24 @@ __device__ inline void write_back(const float *o_l, float p_self, int target, in
 
 // ---- register-resident kernel: every row of the head fits the ring -----------------
 //
-// Requires n_occ <= U * RPI (<= one slot per thread).  Straight-line code: the U
-// key loads of a wave go out first, each buffer is refilled with the matching
-// value row as soon as it has been used, and no load is conditional, so the
-// compiler can wait for exactly the load it needs (vector loads complete in issue
-// order; a load behind a branch would make every later wait conservative).
-// Rounds past the occupied slots re-read the last occupied row and are ignored.
-// The lanes' fp64 partial dot products go to LDS ([row][lane], padded pitch) and
-// thread j adds up row j, so the logit of slot j, its probability, score and
-// position all live in registers of thread j.
+// Requires n_occ <= U * RPI and U * RPW <= 64.  Straight-line code: the U key
+// loads of a wave go out first, each buffer is refilled with the matching value
+// row as soon as it has been used, and no load is conditional, so the compiler
+// can wait for exactly the load it needs (vector loads complete in issue order;
+// a load behind a branch would make every later wait conservative).  Rounds past
+// the occupied slots re-read the last occupied row and are ignored.
+//
+// A wave owns the slots whose rows it reads (U * RPW of them, one per lane): the
+// lanes' fp64 partial dot products go to a wave-private LDS tile and lane l adds
+// up the row of its slot, so a slot's logit, probability, score and position
+// live in registers of one lane and nothing but the softmax normaliser and the
+// final results cross waves: two workgroup barriers per step.
+//
+// Softmax shift: exp(s_j - s_self), the token's own logit, which is known before
+// the key stream arrives (no maximum pass, no barrier for it).  In fp64 this is
+// exact to rounding unless some logit exceeds s_self by ~709; then the
+// normaliser overflows, which is detected, and the step is redone with the true
+// maximum (a rare, workgroup-uniform branch).
 template <int DT, int D, int NW, int U>
 __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
@@ -193,24 +210,25 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     constexpr int LPR = D / EPL;         // lanes per row
     constexpr int RPW = 64 / LPR;        // rows per wave per load
     constexpr int RPI = NW * RPW;        // rows per workgroup-wide round
-    constexpr int ROWS = U * RPI;        // rows the ring covers (<= threads)
+    constexpr int OWN = U * RPW;         // slots a wave owns (one per lane)
     constexpr int PITCH = LPR + 1;       // doubles per row of partials (bank spread)
     constexpr unsigned ROWB = D * sizeof(T);
     static_assert(LPR >= 8 && LPR <= 32, "a row is read by 8, 16 or 32 lanes");
-    static_assert(ROWS <= NW * 64, "one slot per thread");
+    static_assert(OWN <= 64, "one slot per lane");
 
     const int head = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane / LPR, li = lane % LPR;
 
     extern __shared__ __align__(16) unsigned char smem[];
-    double *part_l = reinterpret_cast<double *>(smem);                 // [ROWS][PITCH]
-    double *red_max = part_l + ROWS * PITCH;                           // [NW]
-    double *red_sum = red_max + NW;                                    // [NW]
-    unsigned long long *red_key = reinterpret_cast<unsigned long long *>(red_sum + NW);
-    float *p_l = reinterpret_cast<float *>(red_key + NW);              // [ROWS]
-    float *o_l = p_l + ROWS;                                           // [NW][D]
-    int *target_l = reinterpret_cast<int *>(o_l + NW * D);             // [1]
+    double *part_l = reinterpret_cast<double *>(smem);                 // [NW][OWN][PITCH]
+    double *red_sum = part_l + NW * OWN * PITCH;                       // [NW]
+    double *red_max = red_sum + NW;                                    // [NW] (overflow path)
+    double *red_key = red_max + NW;                                    // [NW]
+    float *p_l = reinterpret_cast<float *>(red_key + NW);              // [NW][OWN]
+    float *o_l = p_l + NW * OWN;                                       // [NW][D]
+    double *part_w = part_l + wave * OWN * PITCH;
+    float *p_w = p_l + wave * OWN;
 
     const size_t hoff = (size_t)head * k;
     char *Kb = Kc + hoff * ROWB;                                       // uniform bases
@@ -221,11 +239,15 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
 
     const int row0 = wave * RPW + sub;   // this lane's row inside a round
     const int last = max(n_occ, 1) - 1;  // clamp target: slot 0 exists even when empty
+    // the slot this lane owns: the row that lane group (lane % RPW) reads in round lane / RPW
+    const int my_slot = (lane / RPW) * RPI + wave * RPW + (lane % RPW);
+    const bool owner = lane < OWN && my_slot < n_occ;
 
-    // q and the new key first: whatever the first arithmetic needs must be
-    // requested before the long key stream
+    // q, the new key and the new value first: whatever the first arithmetic needs
+    // must be requested before the long key stream
     const uint4 qraw = *reinterpret_cast<const uint4 *>(qh + li * EPL);
     const uint4 kraw = *reinterpret_cast<const uint4 *>(knh + li * EPL);
+    const uint4 vraw = *reinterpret_cast<const uint4 *>(vnh + li * EPL);
     unsigned off[U];
     uint4 buf[U];
 #pragma unroll
@@ -233,10 +255,10 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
         off[u] = (unsigned)min(u * RPI + row0, last) * ROWB + (unsigned)li * 16u;
         buf[u] = *reinterpret_cast<const uint4 *>(Kb + off[u]);
     }
-    // slot `tid`'s bookkeeping (unconditional, clamped: a conditional load would
-    // be merged with its default right here and stall on the whole stream)
-    const int pos_j = pos_g[hoff + min(tid, last)];
-    float acc_j = acc_g[hoff + min(tid, last)];
+    // the owned slot's bookkeeping (unconditional, clamped: a conditional load
+    // would be merged with its default right here and stall on the whole stream)
+    const int pos_j = pos_g[hoff + min(my_slot, last)];
+    float acc_j = acc_g[hoff + min(my_slot, last)];
     __builtin_amdgcn_sched_barrier(0);   // every request above leaves before any arithmetic
 
     // this lane's slice of q (widened exactly) and the token's own logit
@@ -265,31 +287,22 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
             a1 = fma((double)E::to_f(x[i + 1]), qd[i + 1], a1);
         }
         buf[u] = *reinterpret_cast<const uint4 *>(Vb + off[u]);   // value row takes the buffer
-        part_l[(u * RPI + row0) * PITCH + li] = a0 + a1;
+        part_w[(u * RPW + sub) * PITCH + li] = a0 + a1;
         __builtin_amdgcn_sched_barrier(0);   // one row at a time: bounds live registers
     }
-    lds_barrier();
+    __builtin_amdgcn_wave_barrier();     // the tile is private to the wave: LDS runs in order
 
     // ---- exact softmax over the occupied slots + the token itself -------------
-    const bool mine = tid < n_occ;       // thread j owns slot j
-    double s_j = -INFINITY;
-    if (mine) {
-        const double *pr = part_l + tid * PITCH;
-        double a = pr[0];
+    double s_j = 0.0;
+    if (lane < OWN) {
+        const double *pr = part_w + lane * PITCH;
+        double a = pr[0], b = pr[1];
 #pragma unroll
-        for (int c = 1; c < LPR; ++c) a += pr[c];
-        s_j = a * scale;
+        for (int c = 2; c < LPR; c += 2) { a += pr[c]; b += pr[c + 1]; }
+        s_j = (a + b) * scale;
     }
-    {
-        const double mw = wave_max(s_j);
-        if (lane == 0) red_max[wave] = mw;
-    }
-    lds_barrier();
-    double mx = s_self;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) mx = fmax(mx, red_max[w]);
-    const double e_j = mine ? exp(s_j - mx) : 0.0;
-    const double e_self = exp(s_self - mx);
+    double e_j = owner ? exp(s_j - s_self) : 0.0;
+    double e_self = 1.0;
     {
         const double dw = wave_sum(e_j);
         if (lane == 0) red_sum[wave] = dw;
@@ -298,52 +311,98 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     double den = e_self;
 #pragma unroll
     for (int w = 0; w < NW; ++w) den += red_sum[w];
+    if (!(den <= 1.79769313486231570815e+308)) {
+        // some logit is > ~709 above the token's own: redo with the true maximum
+        const double mw = wave_max(owner ? s_j : -INFINITY);
+        if (lane == 0) red_max[wave] = mw;
+        lds_barrier();
+        double mx = s_self;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) mx = fmax(mx, red_max[w]);
+        e_j = owner ? exp(s_j - mx) : 0.0;
+        e_self = exp(s_self - mx);
+        const double dw = wave_sum(e_j);
+        if (lane == 0) red_sum[wave] = dw;
+        lds_barrier();
+        den = e_self;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) den += red_sum[w];
+    }
     const float p_self = (float)(e_self / den);
     const float p_j = (float)(e_j / den);
 
-    // ---- score update and eviction candidate ----------------------------------
+    // ---- score update; probabilities to the lanes that read the value rows ----
     acc_j += p_j;                                            // binary32 accumulate
-    if (tid < ROWS) p_l[tid] = p_j;                          // 0 for unoccupied rows
-    unsigned long long key = NO_CANDIDATE;
-    if (mine && pos_j <= t - recent)                         // window after this step = {t-R+1..t}
-        key = ((unsigned long long)__float_as_uint(acc_j) << 32) | (unsigned)pos_j;
-    {
-        const unsigned long long kw = wave_min(key);
-        if (lane == 0) red_key[wave] = kw;
-        if (tid == 0) *target_l = n_occ < k ? n_occ : -1;    // a free slot, if any
-    }
-    lds_barrier();
-    if (n_occ >= k) {
-        // evict the smallest (score, position); with recent == 0 the token itself
-        // competes with its first score and may lose (target stays -1)
-        unsigned long long win = red_key[0];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) win = umin64(win, red_key[w]);
-        const unsigned long long self_key =
-            ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
-        if (key == win && key != NO_CANDIDATE && (recent != 0 || win < self_key))
-            *target_l = tid;                                 // keys are unique (positions are)
-    }
+    if (lane < OWN) p_w[lane] = p_j;                         // 0 for unoccupied rows
+    __builtin_amdgcn_wave_barrier();
 
     // ---- output: one pass over the cached values ------------------------------
     float o[EPL];
+    {
+        // the token's own contribution rides with wave 0's first lane group
+        const float ps = (wave == 0 && sub == 0) ? p_self : 0.f;
+        const T *x = reinterpret_cast<const T *>(&vraw);
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) o[i] = 0.f;
+        for (int i = 0; i < EPL; ++i) o[i] = ps * E::to_f(x[i]);
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float p = p_l[u * RPI + row0];
+        const float p = p_w[u * RPW + sub];
         const T *x = reinterpret_cast<const T *>(&buf[u]);
 #pragma unroll
         for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, E::to_f(x[i]), o[i]);
         __builtin_amdgcn_sched_barrier(0);
     }
     wave_output_to_lds<EPL, LPR, D>(o, o_l, wave, sub, li);
+
+    // ---- eviction candidate: smallest (score, position) outside the window -----
+    // The 64-bit key (score bits, position) of a finite non-negative score is
+    // also a positive double with the same order, and "no candidate" is a NaN,
+    // which fmin drops: the key reduction is a plain fp64 minimum.
+    unsigned long long key = NO_CANDIDATE;
+    if (owner && pos_j <= t - recent)                        // window after this step = {t-R+1..t}
+        key = ((unsigned long long)__float_as_uint(acc_j) << 32) | (unsigned)pos_j;
+    {
+        const double kw = wave_min_f64(__longlong_as_double((long long)key));
+        if (lane == 0) red_key[wave] = kw;
+    }
     lds_barrier();
 
     // ---- write-back -----------------------------------------------------------
-    const int target = *target_l;
-    if (mine && tid != target) acc_g[hoff + tid] = acc_j;
-    write_back<DT, D, NW>(o_l, p_self, target, t, hoff, head, Kb, Vb, acc_g, pos_g, knh, vnh, out_g);
+    if (tid < D) {
+        float r = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) r += o_l[w * D + tid];
+        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r);
+    }
+    // Which slot receives the new token: the first free one if any; else the
+    // evicted one.  With recent == 0 the token itself competes with its first
+    // score and may lose, in which case nothing is written.
+    int tslot = -1;          // wave-uniform: the slot this wave has to fill, if any
+    bool evicted_mine = false;
+    if (n_occ < k) {
+        if (wave == 0) tslot = n_occ;
+    } else {
+        double wd = red_key[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) wd = fmin(wd, red_key[w]);
+        const unsigned long long win = (unsigned long long)__double_as_longlong(wd);
+        const unsigned long long self_key =
+            ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
+        const bool evict = wd == wd && (recent != 0 || win < self_key);
+        evicted_mine = evict && owner && key == win;         // keys are unique (positions are)
+        const unsigned long long b = __ballot(evicted_mine);
+        if (b != 0) tslot = __builtin_amdgcn_readlane(my_slot, __ffsll((long long)b) - 1);
+    }
+    if (owner && !evicted_mine) acc_g[hoff + my_slot] = acc_j;
+    if (tslot >= 0) {
+        if (lane == 0) { pos_g[hoff + tslot] = t; acc_g[hoff + tslot] = p_self; }
+        // lane group 0 holds the new key row, lane group 1 the new value row
+        if (lane < LPR)
+            *reinterpret_cast<uint4 *>(Kb + (size_t)tslot * ROWB + li * 16) = kraw;
+        else if (lane < 2 * LPR)
+            *reinterpret_cast<uint4 *>(Vb + (size_t)tslot * ROWB + li * 16) = vraw;
+    }
 }
 
 // ---- streaming kernel: any budget up to H2O_MAX_BUDGET --------------------------------
@@ -568,9 +627,9 @@ hipError_t launch_resident(const h2o_cache &c, const void *q, const void *kn, co
                            void *out, hipStream_t st)
 {
     constexpr int LPR = D / Elem<DT>::EPL;
-    constexpr int ROWS = U * NW * (64 / LPR);
-    constexpr size_t smem = (size_t)ROWS * (LPR + 1) * 8 + (size_t)NW * 24 + (size_t)ROWS * 4 +
-                            (size_t)NW * D * 4 + 16;
+    constexpr int OWN = U * (64 / LPR);
+    constexpr size_t smem = (size_t)NW * OWN * (LPR + 1) * 8 + (size_t)NW * 24 +
+                            (size_t)NW * OWN * 4 + (size_t)NW * D * 4 + 16;
     auto kern = decode_resident_kernel<DT, D, NW, U>;
     static bool raised = false;
     hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);

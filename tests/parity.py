@@ -121,9 +121,9 @@ def run_gpu_decode(cache, qs, ks, vs, snapshot_heads=None):
 
 
 def check_head_decode(o: OracleHead, qs, ks, vs, outs, snaps, recent, out_tol) -> DecodeStats:
-    out_tol = out_tol + OUT_STORE_SLACK[outs.dtype]
     """Steps one oracle head through T steps and compares with the device's
     per-step outputs [T, d] and slot tables [T, k] of the same head."""
+    out_tol = out_tol + OUT_STORE_SLACK[outs.dtype]
     st = DecodeStats()
     T = qs.shape[0]
     q64, k64, v64, o_gpu = host64(qs), host64(ks), host64(vs), host64(outs)

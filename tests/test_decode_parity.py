@@ -19,7 +19,7 @@ torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 
 def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sample=None,
-             permute_slots=False):
+             permute_slots=False, mutate=None):
     from paper_2306_14048_amd import binding as hb, synth
     dev = torch.device("cuda:0")
     k = heavy + recent
@@ -29,6 +29,8 @@ def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sampl
         rng = np.random.default_rng(seed)
         heads = [heads[i] for i in sorted(rng.choice(len(heads), sample, replace=False))]
     qs, ks, vs = synth.make_steps(B, Hh, d, T, dtype, sigma, dev, seed)
+    if mutate is not None:
+        mutate(qs, ks, vs)                # edits the shared inputs before either side sees them
     cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, scale, device=dev)
     all_heads = [(b, h) for b in range(B) for h in range(Hh)]
     if n > 0:
@@ -122,6 +124,22 @@ def test_decode_short_prompt_then_fill():
 
 def test_decode_explicit_scale():
     run_case(1, 2, 64, 64, 16, 8, 8, torch.float32, 0.75, 21, scale=0.2)
+
+
+@pytest.mark.parametrize("dt,n,heavy,recent", [("f32", 40, 6, 6), ("f16", 700, 300, 333)])
+def test_decode_logits_far_above_the_tokens_own(dt, n, heavy, recent):
+    """Steps whose cached keys score ~1000 above (and below) the token's own
+    logit: exp(s_j - s_self) overflows fp64, so the kernel has to fall back to
+    the true maximum as its softmax shift.  Both kernels (register-resident and
+    streaming) are covered."""
+    def mutate(qs, ks, vs):
+        T = qs.shape[0]
+        for s in range(2, T, 3):
+            qs[s] = 4.0
+            ks[s] = -16.0                 # own logit: 64 * 4 * -16 / 8 = -512
+            if s + 1 < T:
+                ks[s - 1] = 16.0          # the previous token's key scores +512 against it
+    run_case(1, 2, 64, n, 14, heavy, recent, torch_dt[dt], 0.75, 31, mutate=mutate)
 
 
 def test_slot_order_does_not_matter():
