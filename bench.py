@@ -25,6 +25,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per generation-step launch read back from the profiler's FETCH_SIZE /
+# WRITE_SIZE counters (each scaled by what the same counter reports for a plain
+# 256 MiB copy: x2.000 and x1.000), from the runs summarised under profiles/.
+# Counters cannot be collected inside a timed run, so the figure is carried here.
+PROFILED_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 111.2e6}
 
 
 def decode_bytes_per_head_step(k: int, d: int, esize: int) -> int:
@@ -190,8 +195,9 @@ def main():
                    "step": "cache reset + prompt scoring/compression + %d generation steps" % T,
                    "launch": "eager" if graph is None else "hip-graph replay"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "decode_kernel", "bytes_per_launch": bytes_per_launch,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": PROFILED_TRAFFIC_BYTES.get(w.name),
+                     "kernel": "decode_resident_kernel<f16,128,8,13>", "bytes_per_launch": bytes_per_launch,
                      "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager},
         "decode_tokens_per_s": B / (dec_us * 1e-6),
         "prefill_ms": min(prefill_ms),
