@@ -97,29 +97,53 @@ def main():
     k = w.budget
     esize = 4 if w.dtype == torch.float32 else 2
 
-    Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev)
-    qs, ks, vs = synth.make_steps(B, Hh, d, T, w.dtype, w.sigma, dev)
-    outs = torch.empty((T, B, Hh, d), dtype=w.dtype, device=dev)
-    cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
-    ws = cache.workspace(n)
+    L = w.layers
     step_stride = B * Hh * d * esize
-    qp, kp, vp, op = qs.data_ptr(), ks.data_ptr(), vs.data_ptr(), outs.data_ptr()
-    Qp, Kp, Vp, wsp, wsn = Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel()
-    h = cache.handle
+    caches, steps_in = [], []
+    if L == 1:
+        Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev)
+        cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
+        ws = cache.workspace(n)
+        Qp, Kp, Vp, wsp, wsn = Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel()
+        caches.append(cache)
+    else:
+        # a stack of layers: every layer's cache stays resident; prompts are drawn,
+        # scored and compressed one layer at a time before the clock starts (all
+        # layers' prompts together would not fit), and the timed pass is the
+        # generation phase: T token steps, each visiting every layer in turn
+        for layer in range(L):
+            Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev, layer=layer)
+            cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
+            cache.prefill_scores(Q, K, V)
+            torch.cuda.synchronize()
+            cache._ws = None
+            del Q, K, V
+            caches.append(cache)
+    for layer in range(L):
+        steps_in.append(synth.make_steps(B, Hh, d, T, w.dtype, w.sigma, dev, layer=layer))
+    outs = torch.empty((T, B, Hh, d), dtype=w.dtype, device=dev)
+    op = outs.data_ptr()
+    ptrs = [(c.handle, q.data_ptr(), k_.data_ptr(), v.data_ptr()) for c, (q, k_, v) in zip(caches, steps_in)]
 
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
-    def one_pass(stream, timed_events=False):
-        sp = stream.cuda_stream
-        hb.h2o_cache_reset(h, sp)
-        if timed_events:
-            ev[0].record(stream)
-        hb.h2o_prefill_scores(h, Qp, Kp, Vp, n, wsp, wsn, None, sp)
-        if timed_events:
-            ev[1].record(stream)
+    def decode_all(sp):
         for s in range(T):
             off = s * step_stride
-            hb.h2o_decode_step(h, qp + off, kp + off, vp + off, op + off, sp)
+            for (h, qp, kp, vp) in ptrs:
+                hb.h2o_decode_step(h, qp + off, kp + off, vp + off, op + off, sp)
+
+    def one_pass(stream, timed_events=False):
+        sp = stream.cuda_stream
+        if L == 1:
+            hb.h2o_cache_reset(ptrs[0][0], sp)
+        if timed_events:
+            ev[0].record(stream)
+        if L == 1:
+            hb.h2o_prefill_scores(ptrs[0][0], Qp, Kp, Vp, n, wsp, wsn, None, sp)
+        if timed_events:
+            ev[1].record(stream)
+        decode_all(sp)
         if timed_events:
             ev[2].record(stream)
 
@@ -158,28 +182,26 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
 
-        # generation-only timing in the same launch mode (graph of T steps)
+        # generation-only timing in the same launch mode (graph of all step launches)
         dec_graph_us = None
         if graph is not None:
             g2 = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g2, stream=stream):
-                for s in range(T):
-                    off = s * step_stride
-                    hb.h2o_decode_step(h, qp + off, kp + off, vp + off, op + off, stream.cuda_stream)
+                decode_all(stream.cuda_stream)
             g2.replay()
             stream.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 5
+            reps = 5 if L == 1 else 2
             e0.record(stream)
             for _ in range(reps):
                 g2.replay()
             e1.record(stream)
             stream.synchronize()
-            dec_graph_us = e0.elapsed_time(e1) * 1e3 / (reps * T)
+            dec_graph_us = e0.elapsed_time(e1) * 1e3 / (reps * T * L)
 
     ms_per_step = dt * 1e3 / args.steps
     tokens_per_s = B * T / (dt / args.steps)
-    dec_us_eager = min(decode_ms) * 1e3 / T
+    dec_us_eager = min(decode_ms) * 1e3 / (T * L)
     dec_us = dec_graph_us if dec_graph_us is not None else dec_us_eager
     bytes_per_launch = decode_bytes_per_head_step(k, d, esize) * B * Hh
     achieved = bytes_per_launch / (dec_us * 1e-6) / 1e9
@@ -191,16 +213,18 @@ def main():
         "dtype": {torch.float16: "f16", torch.bfloat16: "bf16", torch.float32: "f32"}[w.dtype],
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "heads": Hh, "head_dim": d, "prompt": n,
-                   "decode_steps": T, "budget": k, "heavy": w.heavy, "recent": w.recent,
-                   "step": "cache reset + prompt scoring/compression + %d generation steps" % T,
+                   "decode_steps": T, "layers": L, "budget": k, "heavy": w.heavy, "recent": w.recent,
+                   "step": ("cache reset + prompt scoring/compression + %d generation steps" % T) if L == 1
+                   else ("%d generation steps x %d resident layer caches (prompt phase done before "
+                         "the clock starts)" % (T, L)),
                    "launch": "eager" if graph is None else "hip-graph replay"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": PROFILED_TRAFFIC_BYTES.get(w.name),
-                     "kernel": "decode_resident_kernel<f16,128,8,13>", "bytes_per_launch": bytes_per_launch,
+                     "kernel": "decode_resident_kernel", "bytes_per_launch": bytes_per_launch,
                      "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager},
-        "decode_tokens_per_s": B / (dec_us * 1e-6),
-        "prefill_ms": min(prefill_ms),
+        "decode_tokens_per_s": B / (dec_us * L * 1e-6),
+        "prefill_ms": min(prefill_ms) if L == 1 else None,
     }
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -209,11 +233,12 @@ def main():
         torch.cuda.synchronize()
         dst.copy_(src)                       # the dispatch to read: 256 MiB in, 256 MiB out
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and L == 1:
         heads_total = B * Hh
         rec["cpu_baseline"] = cpu_baseline(w, args.cpu_heads if args.cpu_heads > 0 else heads_total)
     print(json.dumps(rec))
-    cache.close()
+    for c in caches:
+        c.close()
 
 
 if __name__ == "__main__":

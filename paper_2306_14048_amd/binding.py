@@ -240,20 +240,27 @@ class H2OCache:
     def tokens_seen(self) -> int:
         return h2o_cache_tokens_seen(self.handle)
 
-    def kv_views(self):
-        """Tensor views [B, Hh, k, d] of the cached keys and values (aliases of
-        the cache memory, for inspection)."""
+    def views(self):
+        """Tensor views (K, V, acc, pos) of the cache's regions: K, V [B, Hh, k, d]
+        in the cache dtype, acc [B, Hh, k] float32, pos [B, Hh, k] int32.  They
+        alias the cache memory (for inspection and checkpointing)."""
         B, Hh = self.shape_heads
         d, k = self.cfg.head_dim, self.budget
-        kaddr, vaddr, _, _ = h2o_cache_regions(self.handle)
+        kaddr, vaddr, aaddr, paddr = h2o_cache_regions(self.handle)
         base = self.mem.data_ptr()
         es = 4 if self.dtype == torch.float32 else 2
-        cnt = B * Hh * k * d
+        cnt = B * Hh * k
 
-        def view(addr):
+        def view(addr, nbytes, dtype, shape):
             off = addr - base
-            return self.mem[off:off + cnt * es].view(self.dtype).view(B, Hh, k, d)
-        return view(kaddr), view(vaddr)
+            return self.mem[off:off + nbytes].view(dtype).view(shape)
+        return (view(kaddr, cnt * d * es, self.dtype, (B, Hh, k, d)),
+                view(vaddr, cnt * d * es, self.dtype, (B, Hh, k, d)),
+                view(aaddr, cnt * 4, torch.float32, (B, Hh, k)),
+                view(paddr, cnt * 4, torch.int32, (B, Hh, k)))
+
+    def kv_views(self):
+        return self.views()[:2]
 
 
 def prefill_colsum(cfg: h2o_config, Q, K, stream=None) -> torch.Tensor:

@@ -106,16 +106,31 @@ def cache_state_from_oracles(oracles, B, Hh, k, Kp, Vp, base=None):
 
 def run_gpu_decode(cache, qs, ks, vs, snapshot_heads=None):
     """T decode steps through the C ABI, enqueued back to back.  Returns the
-    outputs [T, B, Hh, d] and the slot->position table after every step
-    [T, B, Hh, k] (both on the host)."""
+    outputs and the slot->position table after every step, both on the host:
+    [T, B, Hh, d] and [T, B, Hh, k], or, with `snapshot_heads` = list of (b, h),
+    [T, S, d] and [T, S, k] for those heads only."""
     from paper_2306_14048_amd import binding as hb
     T, B, Hh, d = qs.shape
     k = cache.budget
-    outs = torch.empty((T, B, Hh, d), dtype=qs.dtype, device=qs.device)
-    snaps = torch.empty((T, B, Hh, k), dtype=torch.int32, device=qs.device)
+    dev = qs.device
+    if snapshot_heads is None:
+        outs = torch.empty((T, B, Hh, d), dtype=qs.dtype, device=dev)
+        snaps = torch.empty((T, B, Hh, k), dtype=torch.int32, device=dev)
+        for s in range(T):
+            cache.decode_step(qs[s], ks[s], vs[s], outs[s])
+            hb.h2o_cache_snapshot(cache.handle, snaps[s], None)
+        torch.cuda.synchronize()
+        return outs.cpu(), snaps.cpu()
+    bi = torch.tensor([b for b, _ in snapshot_heads], device=dev)
+    hi = torch.tensor([h for _, h in snapshot_heads], device=dev)
+    pos_view = cache.views()[3]
+    out = torch.empty((B, Hh, d), dtype=qs.dtype, device=dev)
+    outs = torch.empty((T, len(snapshot_heads), d), dtype=qs.dtype, device=dev)
+    snaps = torch.empty((T, len(snapshot_heads), k), dtype=torch.int32, device=dev)
     for s in range(T):
-        cache.decode_step(qs[s], ks[s], vs[s], outs[s])
-        hb.h2o_cache_snapshot(cache.handle, snaps[s], None)
+        cache.decode_step(qs[s], ks[s], vs[s], out)
+        outs[s] = out[bi, hi]
+        snaps[s] = pos_view[bi, hi]
     torch.cuda.synchronize()
     return outs.cpu(), snaps.cpu()
 

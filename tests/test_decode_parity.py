@@ -159,3 +159,67 @@ def test_opt67b_layer_config_all_heads():
     st = run_case(w.batch, w.heads, w.head_dim, w.prompt, w.steps, w.heavy, w.recent, w.dtype,
                   w.sigma, synth.BASE_SEED)
     assert st.head_steps == w.batch * w.heads * w.steps
+
+
+def sampled_case(w, n_sample, seed, steps=None):
+    """Full-size workload on the device, a random sample of heads checked on every
+    step.  All heads go through the device's own prompt phase; the sampled heads'
+    state is then replaced by the oracle's (K/V rows, binary32 scores, positions)
+    so that both sides start those heads from the same state."""
+    from paper_2306_14048_amd import binding as hb, synth
+    dev = torch.device("cuda:0")
+    B, Hh, d, n, k = w.batch, w.heads, w.head_dim, w.prompt, w.budget
+    T = steps or w.steps
+    scale_d = parity.oracle_scale(d)
+    rng = np.random.default_rng(seed)
+    flat = sorted(rng.choice(B * Hh, n_sample, replace=False).tolist())
+    heads = [(i // Hh, i % Hh) for i in flat]
+    Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev, seed)
+    cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
+    cache.prefill_scores(Q, K, V)
+    bi = torch.tensor([b for b, _ in heads]); hi = torch.tensor([h for _, h in heads])
+    Qs, Ks, Vs = Q[bi, hi].cpu(), K[bi, hi].cpu(), V[bi, hi].cpu()          # [S, n, d]
+    del Q, K, V
+    idx_heads = [(0, i) for i in range(n_sample)]
+    oracles, _ = parity.oracle_prefill_heads(Qs[None], Ks[None], Vs[None], idx_heads, w.heavy, w.recent,
+                                             scale_d, cap=n + T)
+    Kc, Vc, acc, pos = parity.cache_state_from_oracles(oracles, 1, n_sample, k, Ks[None], Vs[None])
+    Kv, Vv, av, pv = cache.views()
+    bd, hd = bi.to(dev), hi.to(dev)
+    Kv[bd, hd] = Kc[0].to(dev); Vv[bd, hd] = Vc[0].to(dev)
+    av[bd, hd] = acc[0].to(dev); pv[bd, hd] = pos[0].to(dev)
+    qs, ks, vs = synth.make_steps(B, Hh, d, T, w.dtype, w.sigma, dev, seed)
+    outs, snaps = parity.run_gpu_decode(cache, qs, ks, vs, snapshot_heads=heads)
+    pos_f, acc_f = cache.snapshot()
+    torch.cuda.synchronize()
+    pos_f, acc_f = pos_f[bd, hd].cpu(), acc_f[bd, hd].cpu()
+    qh, kh, vh = qs[:, bd, hd].cpu(), ks[:, bd, hd].cpu(), vs[:, bd, hd].cpu()
+    tol = parity.OUT_TOL[w.dtype]
+
+    def one(i):
+        st = parity.check_head_decode(oracles[(0, i)], qh[:, i], kh[:, i], vh[:, i], outs[:, i],
+                                      snaps[:, i], w.recent, tol)
+        parity.check_final_scores(oracles[(0, i)], pos_f[i], acc_f[i], st)
+        return st
+
+    results, _ = map_heads(one, range(n_sample))
+    total = parity.DecodeStats()
+    for st in results:
+        total.merge(st)
+    print("\n[decode parity, sampled] %s: %d of %d heads x %d steps = %d head-steps, near-tied %d, "
+          "excused %d, max out l2 %.2e linf %.2e, scores not bit-equal %d (max rel %.1e)"
+          % (w.name, n_sample, B * Hh, T, total.head_steps, total.near_tied_steps, total.excused,
+             total.max_out_l2, total.max_out_linf, total.score_mismatch, total.max_score_rel), flush=True)
+    assert total.excused <= int(0.001 * total.head_steps)
+    assert total.max_score_rel <= 1e-6
+    cache.close()
+    return total
+
+
+def test_opt30b_layer_config_sampled_heads():
+    """Workload 4 at full size: batch 64 x 56 heads, d 128, prompt 1024, 1024 steps,
+    budget 103 + 102 held fixed while t grows to 2048, fp16; 64 sampled heads are
+    checked on all 1024 steps."""
+    from paper_2306_14048_amd import synth
+    st = sampled_case(synth.WORKLOADS["opt30b_layer_f16"], 64, synth.BASE_SEED)
+    assert st.head_steps == 64 * 1024
