@@ -51,7 +51,7 @@ __device__ inline f32x16 mma(const uint4 &a, const uint4 &b, f32x16 acc)
 // DT: element type; D: head_dim; MB: 32-row blocks per streamed tile;
 // COLSUM: false = pass 1 (row statistics), true = pass 2 (column sums).
 template <int DT, int D, int MB, bool COLSUM>
-__global__ __launch_bounds__(256) void prefill_pass_kernel(
+__global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
     const char *__restrict__ Qg, const char *__restrict__ Kg, int n, int heads, float c2,
     float *__restrict__ lse2, float *__restrict__ colsum)
 {
@@ -72,8 +72,14 @@ __global__ __launch_bounds__(256) void prefill_pass_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int nblk = (n + SROWS - 1) / SROWS;
-    const int head = blockIdx.x % heads;
-    const int ord = blockIdx.x / heads;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD
+    // has its own L2.  All blocks of a head share the streamed operand, so they
+    // are given consecutive turns on ONE XCD (ids that agree modulo 8): the
+    // operand is then fetched from HBM about once instead of once per block.
+    const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
+    const int head = (turn / nblk) * 8 + xcd;
+    if (head >= heads) return;                       // padding of the last head group
+    const int ord = turn % nblk;
     // heaviest blocks first: pass 1's last row block sees every key tile,
     // pass 2's first key block sees every query tile
     const int blk = COLSUM ? ord : nblk - 1 - ord;
@@ -84,12 +90,17 @@ __global__ __launch_bounds__(256) void prefill_pass_kernel(
     const float *lse_h = lse2 + (size_t)head * n;
 
     const int srow = s0 + wave * 32 + l32;           // this lane's stationary row
+    // Loads are never conditional: a load behind a branch makes the compiler wait
+    // for ALL outstanding loads at the next use of anything, which would expose
+    // the next tile's fetch latency in front of every tile's MFMAs.  Rows past n
+    // are clamped to row n-1 (in bounds) and zeroed after arrival.
     uint4 st[NF];
 #pragma unroll
-    for (int f = 0; f < NF; ++f) {
-        st[f] = make_uint4(0, 0, 0, 0);
-        if (srow < n)
-            st[f] = *reinterpret_cast<const uint4 *>(Sg + (size_t)srow * ROWB + (2 * f + half) * 16);
+    for (int f = 0; f < NF; ++f)
+        st[f] = *reinterpret_cast<const uint4 *>(Sg + (size_t)min(srow, n - 1) * ROWB + (2 * f + half) * 16);
+    if (srow >= n) {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) st[f] = make_uint4(0, 0, 0, 0);
     }
 
     const int ntile_all = (n + BN - 1) / BN;
@@ -98,39 +109,46 @@ __global__ __launch_bounds__(256) void prefill_pass_kernel(
 
     uint4 g[CPT];
     float gl = 0.f;
+    static_assert(CHUNKS % 256 == 0, "every thread moves the same number of chunks");
+    // A head's operand is < 4 GiB (n <= 65536 rows of <= 512 bytes): 32-bit offsets
+    // from the uniform base; a tile is contiguous in memory, chunk `ch` of it sits
+    // at byte ch * 16, and only the last tile needs the row clamp.
+    const unsigned last_row_off = (unsigned)(n - 1) * ROWB;
     auto fetch = [&](int tile) {
+        const unsigned t0 = (unsigned)tile * (BN * ROWB);
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const unsigned ch = tid + c * 256;
+            const unsigned row_off = min(t0 + (ch / CPR) * ROWB, last_row_off);
+            g[c] = *reinterpret_cast<const uint4 *>(Tg + (row_off + (ch % CPR) * 16));
+        }
+        if (COLSUM) gl = lse_h[min(tile * BN + (tid & (BN - 1)), n - 1)];
+    };
+    auto stash = [&](int tile, int buf) {
         const int r0 = tile * BN;
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
             const int ch = tid + c * 256;
             const int r = ch / CPR, cc = ch % CPR;
-            g[c] = make_uint4(0, 0, 0, 0);
-            if (ch < CHUNKS && r0 + r < n)
-                g[c] = *reinterpret_cast<const uint4 *>(Tg + (size_t)(r0 + r) * ROWB + cc * 16);
+            const uint4 v = r0 + r < n ? g[c] : make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(tile_l + buf * TILEB + r * LROW + cc * 16) = v;
         }
-        if (COLSUM && tid < BN) gl = (r0 + tid < n) ? lse_h[r0 + tid] : INFINITY;
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int c = 0; c < CPT; ++c) {
-            const int ch = tid + c * 256;
-            const int r = ch / CPR, cc = ch % CPR;
-            if (ch < CHUNKS)
-                *reinterpret_cast<uint4 *>(tile_l + buf * TILEB + r * LROW + cc * 16) = g[c];
-        }
-        if (COLSUM && tid < BN) lse_l[buf * BN + tid] = gl;
+        if (COLSUM && tid < BN) lse_l[buf * BN + tid] = r0 + tid < n ? gl : INFINITY;
     };
 
     float m_run = -INFINITY, l_run = 0.f;   // pass 1: running max / sum (base 2)
     float c_run = 0.f;                      // pass 2: running column sum
 
-    if (t_begin < t_end) { fetch(t_begin); stash(0); }
+    // every block has at least one tile (s0 < n); the first one is staged here,
+    // which also completes the stationary loads above (loads finish in order)
+    fetch(t_begin);
+    stash(t_begin, 0);
     __syncthreads();
 
     for (int tile = t_begin; tile < t_end; ++tile) {
         const int buf = (tile - t_begin) & 1;
         const bool more = tile + 1 < t_end;
-        if (more) fetch(tile + 1);
+        fetch(more ? tile + 1 : tile);       // unconditional (the last one is a harmless re-read)
 
         f32x16 acc[MB];
 #pragma unroll
@@ -151,57 +169,70 @@ __global__ __launch_bounds__(256) void prefill_pass_kernel(
         const int r0 = tile * BN;
         if constexpr (!COLSUM) {
             // streamed rows are keys j, this lane's row is query i = srow: need j <= i
-            const bool diag = r0 + BN - 1 > s0;          // tile may cross the diagonal
+            // m_run tracks the maximum of the raw products (c2 > 0 keeps the order);
+            // the scale is folded into the exponent's fma
+            if (r0 + BN - 1 > s0) {                      // tile may cross the diagonal: mask
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                        if (j > srow) acc[mb][v] = -INFINITY;
+                    }
+            }
             float mx = m_run;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                    float x = acc[mb][v] * c2;
-                    if (diag && j > srow) x = -INFINITY;
-                    acc[mb][v] = x;
-                    mx = fmaxf(mx, x);
-                }
+                for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, acc[mb][v]), acc[mb][v + 1]);
             const float ms = mx == -INFINITY ? 0.f : mx;
-            float sum = 0.f;
+            const float nms = -ms * c2;
+            float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(acc[mb][v] - ms);
-            l_run = l_run * __builtin_amdgcn_exp2f(m_run - ms) + sum;
+                for (int v = 0; v < 16; v += 2) {
+                    sum0 += __builtin_amdgcn_exp2f(fmaf(acc[mb][v], c2, nms));
+                    sum1 += __builtin_amdgcn_exp2f(fmaf(acc[mb][v + 1], c2, nms));
+                }
+            l_run = l_run * __builtin_amdgcn_exp2f((m_run - ms) * c2) + (sum0 + sum1);
             m_run = mx;
         } else {
             // streamed rows are queries i, this lane's row is key j = srow: need i >= j
             const bool diag = r0 < s0 + SROWS - 1;
             const float *ll = lse_l + buf * BN;
-            float sum = 0.f;
+            float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const float4 l4 = *reinterpret_cast<const float4 *>(ll + mb * 32 + 8 * gq + 4 * half);
                     const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                    float x[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int i = r0 + mb * 32 + 8 * gq + 4 * half + e;
-                        float x = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);   // rows past n: -inf
-                        if (diag && i < srow) x = -INFINITY;
-                        sum += __builtin_amdgcn_exp2f(x);
+                    for (int e = 0; e < 4; ++e)
+                        x[e] = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);       // rows past n: -inf
+                    if (diag) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (r0 + mb * 32 + 8 * gq + 4 * half + e < srow) x[e] = -INFINITY;
                     }
+                    sum0 += __builtin_amdgcn_exp2f(x[0]) + __builtin_amdgcn_exp2f(x[2]);
+                    sum1 += __builtin_amdgcn_exp2f(x[1]) + __builtin_amdgcn_exp2f(x[3]);
                 }
-            c_run += sum;
+            c_run += sum0 + sum1;
         }
 
-        if (more) stash(buf ^ 1);
+        if (more) stash(tile + 1, buf ^ 1);
         __syncthreads();
     }
 
     if constexpr (!COLSUM) {
         const float m2 = __shfl_xor(m_run, 32, 64), l2 = __shfl_xor(l_run, 32, 64);
         const float M = fmaxf(m_run, m2);            // finite: key 0 is visible to every query
-        const float L = l_run * __builtin_amdgcn_exp2f(m_run - M) + l2 * __builtin_amdgcn_exp2f(m2 - M);
-        if (half == 0 && srow < n) lse2[(size_t)head * n + srow] = M + __builtin_amdgcn_logf(L);
+        const float L = l_run * __builtin_amdgcn_exp2f((m_run - M) * c2) +
+                        l2 * __builtin_amdgcn_exp2f((m2 - M) * c2);
+        if (half == 0 && srow < n) lse2[(size_t)head * n + srow] = M * c2 + __builtin_amdgcn_logf(L);
     } else {
         const float c = c_run + __shfl_xor(c_run, 32, 64);
         if (half == 0 && srow < n) colsum[(size_t)head * n + srow] = c;
@@ -220,7 +251,8 @@ hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const
     const int heads = cfg.batch * cfg.heads;
     const int nblk = (n + SROWS - 1) / SROWS;
     const float c2 = (float)(scale * 1.4426950408889634);
-    hipLaunchKernelGGL((prefill_pass_kernel<DT, D, MB, COLSUM>), dim3((unsigned)heads * nblk),
+    hipLaunchKernelGGL((prefill_pass_kernel<DT, D, MB, COLSUM>),
+                       dim3((unsigned)((heads + 7) / 8) * 8 * nblk),
                        dim3(256), smem, st, static_cast<const char *>(Q),
                        static_cast<const char *>(K), n, heads, c2, lse2, colsum);
     return hipGetLastError();
