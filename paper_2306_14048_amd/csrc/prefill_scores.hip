@@ -73,13 +73,19 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
     const int half = lane >> 5, l32 = lane & 31;
     const int nblk = (n + SROWS - 1) / SROWS;
     // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD
-    // has its own L2.  All blocks of a head share the streamed operand, so they
-    // are given consecutive turns on ONE XCD (ids that agree modulo 8): the
-    // operand is then fetched from HBM about once instead of once per block.
+    // has its own L2.  All blocks of a head share the streamed operand, so a head
+    // lives on ONE XCD (ids that agree modulo 8) and its blocks run close together
+    // in time: the operand is then fetched from HBM about once instead of once
+    // per block.  On an XCD, heads are taken in groups of HG (about as many
+    // workgroups as the XCD holds at once); inside a group the order is by block
+    // weight, heaviest first over all its heads, so that the kernel does not end
+    // on a few long blocks.
+    constexpr int HG = 8;
     const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
-    const int head = (turn / nblk) * 8 + xcd;
+    const int group = turn / (HG * nblk), idx = turn % (HG * nblk);
+    const int head = (group * HG + idx % HG) * 8 + xcd;
     if (head >= heads) return;                       // padding of the last head group
-    const int ord = turn % nblk;
+    const int ord = idx / HG;
     // heaviest blocks first: pass 1's last row block sees every key tile,
     // pass 2's first key block sees every query tile
     const int blk = COLSUM ? ord : nblk - 1 - ord;
@@ -252,7 +258,7 @@ hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const
     const int nblk = (n + SROWS - 1) / SROWS;
     const float c2 = (float)(scale * 1.4426950408889634);
     hipLaunchKernelGGL((prefill_pass_kernel<DT, D, MB, COLSUM>),
-                       dim3((unsigned)((heads + 7) / 8) * 8 * nblk),
+                       dim3((unsigned)((heads + 63) / 64) * 64 * nblk),
                        dim3(256), smem, st, static_cast<const char *>(Q),
                        static_cast<const char *>(K), n, heads, c2, lse2, colsum);
     return hipGetLastError();
