@@ -23,6 +23,8 @@
 
 namespace {
 
+#define CPR_OF(rowb) ((rowb) / 16)
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
@@ -48,6 +50,20 @@ __device__ inline f32x16 mma(const uint4 &a, const uint4 &b, f32x16 acc)
     }
 }
 
+// Asynchronous 16-byte-per-lane copy global -> LDS (no registers in between): the
+// wave's 64 lanes fill 1 KiB of LDS starting at the wave-uniform byte offset
+// `lds_base`, lane l at +16*l, each from its own global address.  Written as
+// inline assembly so that the compiler does not order later LDS reads of the
+// OTHER tile buffer behind it; completion is awaited explicitly (dma_wait).
+__device__ inline void dma16(const char *gptr, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory");
+}
+__device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // DT: element type; D: head_dim; MB: 32-row blocks per streamed tile;
 // COLSUM: false = pass 1 (row statistics), true = pass 2 (column sums).
 template <int DT, int D, int MB, bool COLSUM>
@@ -59,8 +75,14 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
     constexpr int ROWB = D * ES;          // bytes per row
     constexpr int NF = ROWB / 32;         // 16-byte fragments per row per lane half
     constexpr int BN = 32 * MB;           // streamed rows per tile
-    constexpr int LROW = ROWB + 16;       // padded LDS row pitch (bank spread)
+    constexpr int LROW = ROWB;            // LDS row pitch (chunks are XOR-swizzled instead of padded)
     constexpr int TILEB = BN * LROW;
+    // Swizzle: 16-byte chunk c of tile row r is stored at chunk position
+    // c ^ key(r), key = low bits of the row (of the row pair for 128-byte rows,
+    // two of which span the banks once), so the 16 or 32 lanes that read the same
+    // chunk of consecutive rows hit different banks.
+    constexpr int RSH = ROWB >= 256 ? 0 : 1;
+    constexpr int KMASK = (CPR_OF(ROWB) < 16 ? CPR_OF(ROWB) : 16) - 1;
     constexpr int CPR = ROWB / 16;        // 16-byte chunks per row
     constexpr int CHUNKS = BN * CPR;      // 16-byte chunks per tile
     constexpr int CPT = (CHUNKS + 255) / 256;
@@ -113,33 +135,36 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
     const int t_begin = COLSUM ? s0 / BN : 0;
     const int t_end = COLSUM ? ntile_all : min(ntile_all, (s0 + SROWS + BN - 1) / BN);
 
-    uint4 g[CPT];
-    float gl = 0.f;
     static_assert(CHUNKS % 256 == 0, "every thread moves the same number of chunks");
-    // A head's operand is < 4 GiB (n <= 65536 rows of <= 512 bytes): 32-bit offsets
-    // from the uniform base; a tile is contiguous in memory, chunk `ch` of it sits
-    // at byte ch * 16, and only the last tile needs the row clamp.
+    // Staging of a streamed tile: copy instruction c of wave w fills LDS chunks
+    // [(c*4 + w)*64, +64) of the buffer; lane l's chunk q = that base + l sits in
+    // tile row q / CPR at position q % CPR and comes from global chunk
+    // (q % CPR) ^ key(row).  A head's operand is < 4 GiB: 32-bit offsets from the
+    // uniform base.  Rows past n are clamped to row n-1 (in bounds); what they
+    // hold is never used (pass 1 masks keys j > i, pass 2 gives them LSE = +inf).
+    unsigned goff[CPT], gchunk[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const unsigned q = (unsigned)(c * 4 + wave) * 64u + lane;
+        const unsigned r = q / CPR, pos = q % CPR;
+        goff[c] = r * ROWB;
+        gchunk[c] = ((pos ^ ((r >> RSH) & KMASK)) * 16u);
+    }
+    // the low 32 bits of a generic pointer into LDS are the LDS byte offset
+    const unsigned lds0 = (unsigned)reinterpret_cast<size_t>(tile_l);
     const unsigned last_row_off = (unsigned)(n - 1) * ROWB;
-    auto fetch = [&](int tile) {
+    float gl = 0.f;
+    auto fetch = [&](int tile, int buf) {
         const unsigned t0 = (unsigned)tile * (BN * ROWB);
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
-            const unsigned ch = tid + c * 256;
-            const unsigned row_off = min(t0 + (ch / CPR) * ROWB, last_row_off);
-            g[c] = *reinterpret_cast<const uint4 *>(Tg + (row_off + (ch % CPR) * 16));
+            const unsigned off = min(t0 + goff[c], last_row_off) + gchunk[c];
+            dma16(Tg + off, __builtin_amdgcn_readfirstlane(lds0 + buf * TILEB + (c * 4 + wave) * 1024));
         }
         if (COLSUM) gl = lse_h[min(tile * BN + (tid & (BN - 1)), n - 1)];
     };
-    auto stash = [&](int tile, int buf) {
-        const int r0 = tile * BN;
-#pragma unroll
-        for (int c = 0; c < CPT; ++c) {
-            const int ch = tid + c * 256;
-            const int r = ch / CPR, cc = ch % CPR;
-            const uint4 v = r0 + r < n ? g[c] : make_uint4(0, 0, 0, 0);
-            *reinterpret_cast<uint4 *>(tile_l + buf * TILEB + r * LROW + cc * 16) = v;
-        }
-        if (COLSUM && tid < BN) lse_l[buf * BN + tid] = r0 + tid < n ? gl : INFINITY;
+    auto stash = [&](int tile, int buf) {          // pass 2 only: the tile's row statistics
+        if (COLSUM && tid < BN) lse_l[buf * BN + tid] = tile * BN + tid < n ? gl : INFINITY;
     };
 
     float m_run = -INFINITY, l_run = 0.f;   // pass 1: running max / sum (base 2)
@@ -147,14 +172,21 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
 
     // every block has at least one tile (s0 < n); the first one is staged here,
     // which also completes the stationary loads above (loads finish in order)
-    fetch(t_begin);
+    fetch(t_begin, 0);
     stash(t_begin, 0);
+    dma_wait();
+    // tell the compiler that the stationary fragments have arrived (it cannot see
+    // the wait above), or it would re-wait for them, and with them for the tile
+    // copies in flight, in front of the MFMAs of every iteration
+#pragma unroll
+    for (int f = 0; f < NF; ++f)
+        asm volatile("" ::"v"(st[f].x), "v"(st[f].y), "v"(st[f].z), "v"(st[f].w));
     __syncthreads();
 
     for (int tile = t_begin; tile < t_end; ++tile) {
         const int buf = (tile - t_begin) & 1;
         const bool more = tile + 1 < t_end;
-        fetch(more ? tile + 1 : tile);       // unconditional (the last one is a harmless re-read)
+        fetch(more ? tile + 1 : tile, buf ^ 1);   // unconditional (the last one is a harmless re-read)
 
         f32x16 acc[MB];
 #pragma unroll
@@ -166,8 +198,9 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
         for (int f = 0; f < NF; ++f) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
+                const int row = mb * 32 + l32;
                 const uint4 a = *reinterpret_cast<const uint4 *>(
-                    tb + (mb * 32 + l32) * LROW + (2 * f + half) * 16);
+                    tb + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
                 acc[mb] = mma<DT>(a, st[f], acc[mb]);
             }
         }
@@ -230,6 +263,7 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
         }
 
         if (more) stash(tile + 1, buf ^ 1);
+        dma_wait();
         __syncthreads();
     }
 
@@ -252,7 +286,7 @@ hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const
     constexpr int ES = DT == H2O_F32 ? 4 : 2;
     constexpr int MB = (D * ES >= 512) ? 1 : 2;      // keep the two tile buffers under 48 KiB
     constexpr int BN = 32 * MB;
-    constexpr size_t smem = 2 * (size_t)BN * (D * ES + 16) + 2 * BN * sizeof(float);
+    constexpr size_t smem = 2 * (size_t)BN * (D * ES) + 2 * BN * sizeof(float);
     static_assert(smem <= 48 * 1024, "tile buffers must fit the default LDS limit");
     const int heads = cfg.batch * cfg.heads;
     const int nblk = (n + SROWS - 1) / SROWS;
