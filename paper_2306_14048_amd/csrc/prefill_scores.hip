@@ -7,10 +7,14 @@
 //   pass 2 (column sums)    : c_j   = sum_{i>=j} exp(scale * <Q_i, K_j> - LSE_i)
 //
 // Both passes are the same dense contraction QK^T and run on the matrix cores;
-// they differ in which operand stays in registers.  A workgroup of 4 waves owns
-// 128 "stationary" rows (queries in pass 1, keys in pass 2; 32 per wave, kept in
-// registers as MFMA B-operand fragments) and streams tiles of the other operand
-// through LDS (double buffered) as A-operand fragments.  With the 32x32 MFMA
+// they differ in which operand stays in registers.  A workgroup of NWV waves owns
+// 32*NWV "stationary" rows (queries in pass 1, keys in pass 2; 32 per wave, kept
+// in registers as MFMA B-operand fragments) and streams tiles of the other
+// operand through LDS (double buffered) as A-operand fragments.  Eight waves
+// share one streamed tile: the copy into LDS and its address arithmetic are paid
+// once per 256 stationary rows, which matters because the matrix pipe, the
+// vector ALU (one exponential per product) and the vector memory path are all
+// close to saturated by this loop.  With the 32x32 MFMA
 // result layout a lane then holds one stationary row's products with 16 streamed
 // rows per tile, so the reduction each pass needs (over keys for the row
 // statistics, over queries for the column sums) runs inside a lane across the
@@ -20,6 +24,7 @@
 // Everything is computed in base 2: x = (scale*log2 e) * <q,k>, the stored row
 // statistic is log2 of the row's normaliser.
 #include "h2o_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -29,7 +34,6 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int SROWS = 128;     // stationary rows per workgroup (4 waves x 32)
 
 template <int DT>
 __device__ inline f32x16 mma(const uint4 &a, const uint4 &b, f32x16 acc)
@@ -52,22 +56,37 @@ __device__ inline f32x16 mma(const uint4 &a, const uint4 &b, f32x16 acc)
 
 // Asynchronous 16-byte-per-lane copy global -> LDS (no registers in between): the
 // wave's 64 lanes fill 1 KiB of LDS starting at the wave-uniform byte offset
-// `lds_base`, lane l at +16*l, each from its own global address.  Written as
-// inline assembly so that the compiler does not order later LDS reads of the
-// OTHER tile buffer behind it; completion is awaited explicitly (dma_wait).
-__device__ inline void dma16(const char *gptr, unsigned lds_base)
+// `lds_base`, lane l at +16*l, each from byte `voff + soff` of the buffer that
+// `rsrc` describes (voff per lane, soff wave-uniform: the per-tile advance costs
+// no vector instruction).  Written as inline assembly so that the compiler does
+// not order later LDS reads of the OTHER tile buffer behind it; completion is
+// awaited explicitly (dma_wait).
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ inline void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
                  :
-                 : "v"(gptr), "s"(lds_base)
+                 : "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_base)
                  : "memory");
+}
+// Raw buffer descriptor (no stride, no swizzle, 32-bit data format) over `bytes`
+// bytes at `base`; reads past the end return zero.
+__device__ inline i32x4 make_rsrc(const void *base, unsigned bytes)
+{
+    const size_t b = reinterpret_cast<size_t>(base);
+    i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
+    r.w = 0x00020000;
+    return r;
 }
 __device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// DT: element type; D: head_dim; MB: 32-row blocks per streamed tile;
-// COLSUM: false = pass 1 (row statistics), true = pass 2 (column sums).
-template <int DT, int D, int MB, bool COLSUM>
-__global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
+// DT: element type; D: head_dim; MB: 32-row blocks per streamed tile; NWV: waves
+// per workgroup; COLSUM: false = pass 1 (row statistics), true = pass 2 (column sums).
+template <int DT, int D, int MB, int NWV, bool COLSUM>
+__global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     const char *__restrict__ Qg, const char *__restrict__ Kg, int n, int heads, float c2,
     float *__restrict__ lse2, float *__restrict__ colsum)
 {
@@ -85,7 +104,9 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
     constexpr int KMASK = (CPR_OF(ROWB) < 16 ? CPR_OF(ROWB) : 16) - 1;
     constexpr int CPR = ROWB / 16;        // 16-byte chunks per row
     constexpr int CHUNKS = BN * CPR;      // 16-byte chunks per tile
-    constexpr int CPT = (CHUNKS + 255) / 256;
+    constexpr int NT = NWV * 64;          // threads per workgroup
+    constexpr int SROWS = NWV * 32;       // stationary rows per workgroup
+    constexpr int CPT = CHUNKS / NT;      // copy instructions per wave per tile
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *tile_l = smem;                                      // [2][TILEB]
@@ -135,31 +156,39 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
     const int t_begin = COLSUM ? s0 / BN : 0;
     const int t_end = COLSUM ? ntile_all : min(ntile_all, (s0 + SROWS + BN - 1) / BN);
 
-    static_assert(CHUNKS % 256 == 0, "every thread moves the same number of chunks");
+    static_assert(CHUNKS % NT == 0 && CPT >= 1, "every thread moves the same number of chunks");
     // Staging of a streamed tile: copy instruction c of wave w fills LDS chunks
-    // [(c*4 + w)*64, +64) of the buffer; lane l's chunk q = that base + l sits in
+    // [(c*NWV + w)*64, +64) of the buffer; lane l's chunk q = that base + l sits in
     // tile row q / CPR at position q % CPR and comes from global chunk
-    // (q % CPR) ^ key(row).  A head's operand is < 4 GiB: 32-bit offsets from the
-    // uniform base.  Rows past n are clamped to row n-1 (in bounds); what they
-    // hold is never used (pass 1 masks keys j > i, pass 2 gives them LSE = +inf).
+    // (q % CPR) ^ key(row).  A head's operand is < 4 GiB: a 32-bit per-lane offset
+    // inside the tile plus the tile's wave-uniform offset.  Rows past n (only in a
+    // ragged last tile) are clamped to row n-1; what they hold is never used
+    // (pass 1 masks keys j > i, pass 2 gives them LSE = +inf).
     unsigned goff[CPT], gchunk[CPT];
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
-        const unsigned q = (unsigned)(c * 4 + wave) * 64u + lane;
+        const unsigned q = (unsigned)(c * NWV + wave) * 64u + lane;
         const unsigned r = q / CPR, pos = q % CPR;
         goff[c] = r * ROWB;
         gchunk[c] = ((pos ^ ((r >> RSH) & KMASK)) * 16u);
     }
+    const i32x4 rsrc = make_rsrc(Tg, (unsigned)n * ROWB);
     // the low 32 bits of a generic pointer into LDS are the LDS byte offset
     const unsigned lds0 = (unsigned)reinterpret_cast<size_t>(tile_l);
     const unsigned last_row_off = (unsigned)(n - 1) * ROWB;
+    const unsigned lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
     float gl = 0.f;
     auto fetch = [&](int tile, int buf) {
         const unsigned t0 = (unsigned)tile * (BN * ROWB);
+        if (t0 + BN * ROWB <= (unsigned)n * ROWB) {            // whole tile inside the operand
 #pragma unroll
-        for (int c = 0; c < CPT; ++c) {
-            const unsigned off = min(t0 + goff[c], last_row_off) + gchunk[c];
-            dma16(Tg + off, __builtin_amdgcn_readfirstlane(lds0 + buf * TILEB + (c * 4 + wave) * 1024));
+            for (int c = 0; c < CPT; ++c)
+                dma16(rsrc, goff[c] + gchunk[c], t0, lds_w + buf * TILEB + c * NWV * 1024);
+        } else {
+#pragma unroll
+            for (int c = 0; c < CPT; ++c)
+                dma16(rsrc, min(t0 + goff[c], last_row_off) + gchunk[c], 0u,
+                      lds_w + buf * TILEB + c * NWV * 1024);
         }
         if (COLSUM) gl = lse_h[min(tile * BN + (tid & (BN - 1)), n - 1)];
     };
@@ -183,88 +212,109 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
         asm volatile("" ::"v"(st[f].x), "v"(st[f].y), "v"(st[f].z), "v"(st[f].w));
     __syncthreads();
 
-    for (int tile = t_begin; tile < t_end; ++tile) {
+    // One streamed tile.  MASKED = the tile touches the causal diagonal of this
+    // workgroup's rows; those tiles run in a loop of their own so that the tiles
+    // away from the diagonal (most of them) carry no masking arithmetic at all.
+    // In a masked tile a wave whose 32 rows see none of the tile's rows skips the
+    // arithmetic (it still copies its share of the next tile and meets the barrier).
+    auto tile_step = [&](int tile, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         const int buf = (tile - t_begin) & 1;
         const bool more = tile + 1 < t_end;
         fetch(more ? tile + 1 : tile, buf ^ 1);   // unconditional (the last one is a harmless re-read)
-
-        f32x16 acc[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
-        const unsigned char *tb = tile_l + buf * TILEB;
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const int row = mb * 32 + l32;
-                const uint4 a = *reinterpret_cast<const uint4 *>(
-                    tb + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
-                acc[mb] = mma<DT>(a, st[f], acc[mb]);
-            }
-        }
-
         const int r0 = tile * BN;
-        if constexpr (!COLSUM) {
-            // streamed rows are keys j, this lane's row is query i = srow: need j <= i
-            // m_run tracks the maximum of the raw products (c2 > 0 keeps the order);
-            // the scale is folded into the exponent's fma
-            if (r0 + BN - 1 > s0) {                      // tile may cross the diagonal: mask
+        const int w0 = s0 + wave * 32;            // first stationary row of this wave
+        // pass 1: keys r0.. are visible to queries >= r0; pass 2: queries up to
+        // r0+BN-1 see keys <= r0+BN-1
+        const bool live = !MASKED || (COLSUM ? r0 + BN - 1 >= w0 : r0 <= w0 + 31);
+        if (live) {
+            f32x16 acc[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+            const unsigned char *tb = tile_l + buf * TILEB;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int row = mb * 32 + l32;
+                    const uint4 a = *reinterpret_cast<const uint4 *>(
+                        tb + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
+                    acc[mb] = mma<DT>(a, st[f], acc[mb]);
+                }
+            }
+
+            if constexpr (!COLSUM) {
+                // streamed rows are keys j, this lane's row is query i = srow: need j <= i.
+                // m_run tracks the maximum of the raw products (c2 > 0 keeps the order);
+                // the scale is folded into the exponent's fma
+                if constexpr (MASKED) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                            if (j > srow) acc[mb][v] = -INFINITY;
+                        }
+                }
+                float mx = m_run;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                        if (j > srow) acc[mb][v] = -INFINITY;
+                    for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, acc[mb][v]), acc[mb][v + 1]);
+                const float ms = mx == -INFINITY ? 0.f : mx;
+                const float nms = -ms * c2;
+                float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; v += 2) {
+                        sum0 += __builtin_amdgcn_exp2f(fmaf(acc[mb][v], c2, nms));
+                        sum1 += __builtin_amdgcn_exp2f(fmaf(acc[mb][v + 1], c2, nms));
                     }
-            }
-            float mx = m_run;
+                l_run = l_run * __builtin_amdgcn_exp2f((m_run - ms) * c2) + (sum0 + sum1);
+                m_run = mx;
+            } else {
+                // streamed rows are queries i, this lane's row is key j = srow: need i >= j
+                const float *ll = lse_l + buf * BN;
+                float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+                for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, acc[mb][v]), acc[mb][v + 1]);
-            const float ms = mx == -INFINITY ? 0.f : mx;
-            const float nms = -ms * c2;
-            float sum0 = 0.f, sum1 = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; v += 2) {
-                    sum0 += __builtin_amdgcn_exp2f(fmaf(acc[mb][v], c2, nms));
-                    sum1 += __builtin_amdgcn_exp2f(fmaf(acc[mb][v + 1], c2, nms));
-                }
-            l_run = l_run * __builtin_amdgcn_exp2f((m_run - ms) * c2) + (sum0 + sum1);
-            m_run = mx;
-        } else {
-            // streamed rows are queries i, this lane's row is key j = srow: need i >= j
-            const bool diag = r0 < s0 + SROWS - 1;
-            const float *ll = lse_l + buf * BN;
-            float sum0 = 0.f, sum1 = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const float4 l4 = *reinterpret_cast<const float4 *>(ll + mb * 32 + 8 * gq + 4 * half);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                    float x[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        x[e] = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);       // rows past n: -inf
-                    if (diag) {
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const float4 l4 = *reinterpret_cast<const float4 *>(ll + mb * 32 + 8 * gq + 4 * half);
+                        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                        float x[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (r0 + mb * 32 + 8 * gq + 4 * half + e < srow) x[e] = -INFINITY;
+                            x[e] = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);       // rows past n: -inf
+                        if constexpr (MASKED) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (r0 + mb * 32 + 8 * gq + 4 * half + e < srow) x[e] = -INFINITY;
+                        }
+                        sum0 += __builtin_amdgcn_exp2f(x[0]) + __builtin_amdgcn_exp2f(x[2]);
+                        sum1 += __builtin_amdgcn_exp2f(x[1]) + __builtin_amdgcn_exp2f(x[3]);
                     }
-                    sum0 += __builtin_amdgcn_exp2f(x[0]) + __builtin_amdgcn_exp2f(x[2]);
-                    sum1 += __builtin_amdgcn_exp2f(x[1]) + __builtin_amdgcn_exp2f(x[3]);
-                }
-            c_run += sum0 + sum1;
+                c_run += sum0 + sum1;
+            }
         }
 
         if (more) stash(tile + 1, buf ^ 1);
         dma_wait();
         __syncthreads();
+    };
+    // SROWS is a multiple of BN, so the tiles that touch the diagonal are exactly
+    // those that overlap this workgroup's own rows [s0, s0 + SROWS)
+    static_assert(SROWS % BN == 0, "diagonal tiles are whole");
+    const int t_diag0 = s0 / BN, t_diag1 = min(t_end, (s0 + SROWS) / BN);
+    if constexpr (!COLSUM) {
+        for (int tile = t_begin; tile < t_diag0; ++tile) tile_step(tile, std::false_type{});
+        for (int tile = t_diag0; tile < t_end; ++tile) tile_step(tile, std::true_type{});
+    } else {
+        for (int tile = t_begin; tile < t_diag1; ++tile) tile_step(tile, std::true_type{});
+        for (int tile = t_diag1; tile < t_end; ++tile) tile_step(tile, std::false_type{});
     }
 
     if constexpr (!COLSUM) {
@@ -279,10 +329,11 @@ __global__ __launch_bounds__(256, 4) void prefill_pass_kernel(
     }
 }
 
-template <int DT, int D, bool COLSUM>
+template <int DT, int D, int NWV, bool COLSUM>
 hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
                        float *lse2, float *colsum, hipStream_t st)
 {
+    constexpr int SROWS = NWV * 32;
     constexpr int ES = DT == H2O_F32 ? 4 : 2;
     constexpr int MB = (D * ES >= 512) ? 1 : 2;      // keep the two tile buffers under 48 KiB
     constexpr int BN = 32 * MB;
@@ -291,13 +342,16 @@ hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const
     const int heads = cfg.batch * cfg.heads;
     const int nblk = (n + SROWS - 1) / SROWS;
     const float c2 = (float)(scale * 1.4426950408889634);
-    hipLaunchKernelGGL((prefill_pass_kernel<DT, D, MB, COLSUM>),
+    hipLaunchKernelGGL((prefill_pass_kernel<DT, D, MB, NWV, COLSUM>),
                        dim3((unsigned)((heads + 63) / 64) * 64 * nblk),
-                       dim3(256), smem, st, static_cast<const char *>(Q),
+                       dim3(NWV * 64), smem, st, static_cast<const char *>(Q),
                        static_cast<const char *>(K), n, heads, c2, lse2, colsum);
     return hipGetLastError();
 }
 
+#ifndef PREFILL_WAVES
+#define PREFILL_WAVES 8
+#endif
 template <bool COLSUM>
 hipError_t dispatch(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
                     float *lse2, float *colsum, hipStream_t st)
@@ -305,14 +359,14 @@ hipError_t dispatch(const h2o_config &cfg, double scale, const void *Q, const vo
     const int d = cfg.head_dim;
     switch (cfg.dtype) {
     case H2O_F32:
-        return d == 64 ? launch_pass<H2O_F32, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_F32, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_F32, 64, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_F32, 128, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
     case H2O_F16:
-        return d == 64 ? launch_pass<H2O_F16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_F16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_F16, 64, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_F16, 128, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
     default:
-        return d == 64 ? launch_pass<H2O_BF16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_BF16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_BF16, 64, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_BF16, 128, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
     }
 }
 
