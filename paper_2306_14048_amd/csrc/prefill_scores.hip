@@ -81,11 +81,42 @@ __device__ inline i32x4 make_rsrc(const void *base, unsigned bytes)
     r.w = 0x00020000;
     return r;
 }
-__device__ inline void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Same for one dword per lane (lane l writes LDS word l from `lds_base`); lanes
+// that are switched off copy nothing.
+__device__ inline void dma4(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dword %0, %1, %2 offen lds"
+                 :
+                 : "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_base)
+                 : "memory");
+}
 
-// DT: element type; D: head_dim; MB: 32-row blocks per streamed tile; NWV: waves
-// per workgroup; COLSUM: false = pass 1 (row statistics), true = pass 2 (column sums).
-template <int DT, int D, int MB, int NWV, bool COLSUM>
+// Waits until at most N of this wave's vector-memory requests are outstanding.
+template <int N> __device__ inline void dma_wait_upto()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Workgroup barrier that first drains this wave's LDS reads (so that a buffer is
+// really free once every wave has passed) but leaves global requests in flight.
+__device__ inline void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+constexpr int NWV = 8;         // waves per workgroup
+constexpr int NTB = 3;         // streamed-tile buffers (copies run two tiles ahead)
+constexpr int NLB = 4;         // row-statistic buffers (pass 2; read one phase later than the tile)
+
+// DT: element type; D: head_dim; MB: 32-row blocks per streamed tile;
+// COLSUM: false = pass 1 (row statistics), true = pass 2 (column sums).
+//
+// Schedule.  Per streamed tile a wave has a matrix phase (16 MFMAs fed from LDS)
+// and a vector phase (scale, exponential and sum of its 32x64 products), about
+// equally long.  A SIMD runs both pipes at once only if its waves are in
+// different phases, and waves that start together and meet at a barrier per
+// tile stay in the same phase.  The eight waves therefore form two groups of
+// four (wave w and w+4 sit on the same SIMD) that are kept one phase apart by
+// the barriers themselves: the second group enters the loop one barrier late,
+// so whenever one group is in its matrix phase the other is in its vector
+// phase ("ping-pong").  s_setprio lets the matrix phase win the issue slot.
+template <int DT, int D, int MB, bool COLSUM>
 __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     const char *__restrict__ Qg, const char *__restrict__ Kg, int n, int heads, float c2,
     float *__restrict__ lse2, float *__restrict__ colsum)
@@ -106,14 +137,19 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     constexpr int CHUNKS = BN * CPR;      // 16-byte chunks per tile
     constexpr int NT = NWV * 64;          // threads per workgroup
     constexpr int SROWS = NWV * 32;       // stationary rows per workgroup
-    constexpr int CPT = CHUNKS / NT;      // copy instructions per wave per tile
+    constexpr int CPT = CHUNKS / NT;      // tile-copy instructions per wave per tile
+    constexpr int CPF = CPT + (COLSUM ? 1 : 0);   // copy instructions per wave per fetch
+    constexpr int LPW = BN / NWV;         // row statistics each wave copies per tile
+    static_assert(CHUNKS % NT == 0 && CPT >= 1, "every thread moves the same number of chunks");
+    static_assert(SROWS % BN == 0 && BN % NWV == 0, "tiles divide the workgroup's rows");
 
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *tile_l = smem;                                      // [2][TILEB]
-    float *lse_l = reinterpret_cast<float *>(smem + 2 * TILEB);        // [2][BN] (pass 2)
+    unsigned char *tile_l = smem;                                        // [NTB][TILEB]
+    float *lse_l = reinterpret_cast<float *>(smem + NTB * TILEB);        // [NLB][BN] (pass 2)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
+    const int grp = wave >> 2;            // ping-pong group
     const int nblk = (n + SROWS - 1) / SROWS;
     // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD
     // has its own L2.  All blocks of a head share the streamed operand, so a head
@@ -136,13 +172,9 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     const size_t hbase = (size_t)head * n * ROWB;
     const char *Sg = (COLSUM ? Kg : Qg) + hbase;     // stationary operand
     const char *Tg = (COLSUM ? Qg : Kg) + hbase;     // streamed operand
-    const float *lse_h = lse2 + (size_t)head * n;
 
     const int srow = s0 + wave * 32 + l32;           // this lane's stationary row
-    // Loads are never conditional: a load behind a branch makes the compiler wait
-    // for ALL outstanding loads at the next use of anything, which would expose
-    // the next tile's fetch latency in front of every tile's MFMAs.  Rows past n
-    // are clamped to row n-1 (in bounds) and zeroed after arrival.
+    // Rows past n are clamped to row n-1 (in bounds) and zeroed after arrival.
     uint4 st[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f)
@@ -154,16 +186,17 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
 
     const int ntile_all = (n + BN - 1) / BN;
     const int t_begin = COLSUM ? s0 / BN : 0;
-    const int t_end = COLSUM ? ntile_all : min(ntile_all, (s0 + SROWS + BN - 1) / BN);
+    const int t_end = COLSUM ? ntile_all : min(ntile_all, (s0 + SROWS) / BN);
 
-    static_assert(CHUNKS % NT == 0 && CPT >= 1, "every thread moves the same number of chunks");
     // Staging of a streamed tile: copy instruction c of wave w fills LDS chunks
     // [(c*NWV + w)*64, +64) of the buffer; lane l's chunk q = that base + l sits in
     // tile row q / CPR at position q % CPR and comes from global chunk
     // (q % CPR) ^ key(row).  A head's operand is < 4 GiB: a 32-bit per-lane offset
     // inside the tile plus the tile's wave-uniform offset.  Rows past n (only in a
     // ragged last tile) are clamped to row n-1; what they hold is never used
-    // (pass 1 masks keys j > i, pass 2 gives them LSE = +inf).
+    // (both passes mask them).  Pass 2 also copies the tile's BN row statistics,
+    // LPW lanes of every wave taking LPW of them, so that every wave issues the
+    // same number of copy instructions per tile and one wait count fits all.
     unsigned goff[CPT], gchunk[CPT];
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
@@ -173,78 +206,101 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
         gchunk[c] = ((pos ^ ((r >> RSH) & KMASK)) * 16u);
     }
     const i32x4 rsrc = make_rsrc(Tg, (unsigned)n * ROWB);
+    const i32x4 rsrc_lse = make_rsrc(lse2 + (size_t)head * n, (unsigned)n * 4u);
     // the low 32 bits of a generic pointer into LDS are the LDS byte offset
-    const unsigned lds0 = (unsigned)reinterpret_cast<size_t>(tile_l);
+    const unsigned lds_w = __builtin_amdgcn_readfirstlane(
+        (unsigned)reinterpret_cast<size_t>(tile_l) + wave * 1024);
+    const unsigned lds_lse = (unsigned)reinterpret_cast<size_t>(lse_l);
     const unsigned last_row_off = (unsigned)(n - 1) * ROWB;
-    const unsigned lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
-    float gl = 0.f;
-    auto fetch = [&](int tile, int buf) {
+    const bool lse_lane = lane / LPW == wave;        // (lane < BN follows from wave < NWV)
+    // i = index of the tile in this block's sequence (selects the buffers)
+    auto fetch = [&](int tile, int tb, int lb) {
         const unsigned t0 = (unsigned)tile * (BN * ROWB);
         if (t0 + BN * ROWB <= (unsigned)n * ROWB) {            // whole tile inside the operand
 #pragma unroll
             for (int c = 0; c < CPT; ++c)
-                dma16(rsrc, goff[c] + gchunk[c], t0, lds_w + buf * TILEB + c * NWV * 1024);
+                dma16(rsrc, goff[c] + gchunk[c], t0, lds_w + tb * TILEB + c * NWV * 1024);
         } else {
 #pragma unroll
             for (int c = 0; c < CPT; ++c)
                 dma16(rsrc, min(t0 + goff[c], last_row_off) + gchunk[c], 0u,
-                      lds_w + buf * TILEB + c * NWV * 1024);
+                      lds_w + tb * TILEB + c * NWV * 1024);
         }
-        if (COLSUM) gl = lse_h[min(tile * BN + (tid & (BN - 1)), n - 1)];
-    };
-    auto stash = [&](int tile, int buf) {          // pass 2 only: the tile's row statistics
-        if (COLSUM && tid < BN) lse_l[buf * BN + tid] = tile * BN + tid < n ? gl : INFINITY;
+        if constexpr (COLSUM) {
+            // lane l writes LDS word l of the buffer; statistics past n read as 0
+            // (end of the descriptor) or as the next head's and are masked later
+            if (lse_lane) dma4(rsrc_lse, (unsigned)lane * 4u, (unsigned)tile * (BN * 4u), lds_lse + lb * (BN * 4));
+        }
     };
 
     float m_run = -INFINITY, l_run = 0.f;   // pass 1: running max / sum (base 2)
     float c_run = 0.f;                      // pass 2: running column sum
 
-    // every block has at least one tile (s0 < n); the first one is staged here,
-    // which also completes the stationary loads above (loads finish in order)
-    fetch(t_begin, 0);
-    stash(t_begin, 0);
-    dma_wait();
+    // Every block has at least one tile (s0 < n).  The first two are requested
+    // here; waiting for the first also completes the stationary loads above
+    // (vector loads finish in order).  Requests past the block's last tile repeat
+    // that tile (harmless, keeps the request count per iteration constant).
+    fetch(t_begin, 0, 0);
+    fetch(min(t_begin + 1, t_end - 1), 1, 1);
+    dma_wait_upto<CPF>();
     // tell the compiler that the stationary fragments have arrived (it cannot see
     // the wait above), or it would re-wait for them, and with them for the tile
     // copies in flight, in front of the MFMAs of every iteration
 #pragma unroll
     for (int f = 0; f < NF; ++f)
         asm volatile("" ::"v"(st[f].x), "v"(st[f].y), "v"(st[f].z), "v"(st[f].w));
-    __syncthreads();
+    wg_barrier();
+    if (grp == 1) wg_barrier();            // second group runs one phase behind
 
+    int tb = 0, lb = 0;                    // buffers of the current tile
     // One streamed tile.  MASKED = the tile touches the causal diagonal of this
-    // workgroup's rows; those tiles run in a loop of their own so that the tiles
-    // away from the diagonal (most of them) carry no masking arithmetic at all.
-    // In a masked tile a wave whose 32 rows see none of the tile's rows skips the
-    // arithmetic (it still copies its share of the next tile and meets the barrier).
+    // workgroup's rows or runs past the prompt's end; those tiles run in loops of
+    // their own so that the others (most) carry no masking arithmetic at all.
+    // In a diagonal tile a wave whose 32 rows see none of the tile's rows skips
+    // the arithmetic (it still copies its share of a later tile and meets the
+    // barriers).
+    //
+    // Buffer life times: the tile two ahead is requested at the start of the
+    // matrix phase into the buffer of the previous tile, which both groups have
+    // finished reading (the later group's matrix phase of that tile ended at the
+    // barrier this group has just passed).  Row statistics are read in the vector
+    // phase, one barrier later, hence one buffer more.  Before either barrier a
+    // wave waits until only its newest request is outstanding, so that by the
+    // barrier in front of any matrix phase every wave's share of that tile has
+    // landed.
     auto tile_step = [&](int tile, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const int buf = (tile - t_begin) & 1;
-        const bool more = tile + 1 < t_end;
-        fetch(more ? tile + 1 : tile, buf ^ 1);   // unconditional (the last one is a harmless re-read)
+        const int tb2 = tb == 0 ? NTB - 1 : tb - 1;               // (tb + 2) % 3
+        fetch(min(tile + 2, t_end - 1), tb2, (lb + 2) & (NLB - 1));
         const int r0 = tile * BN;
         const int w0 = s0 + wave * 32;            // first stationary row of this wave
         // pass 1: keys r0.. are visible to queries >= r0; pass 2: queries up to
         // r0+BN-1 see keys <= r0+BN-1
         const bool live = !MASKED || (COLSUM ? r0 + BN - 1 >= w0 : r0 <= w0 + 31);
+        f32x16 acc[MB];
         if (live) {
-            f32x16 acc[MB];
+            __builtin_amdgcn_s_setprio(2);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
-            const unsigned char *tb = tile_l + buf * TILEB;
+            const unsigned char *tbp = tile_l + tb * TILEB;
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
                     const int row = mb * 32 + l32;
                     const uint4 a = *reinterpret_cast<const uint4 *>(
-                        tb + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
+                        tbp + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
                     acc[mb] = mma<DT>(a, st[f], acc[mb]);
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
+        }
+        dma_wait_upto<CPF>();
+        wg_barrier();
 
+        if (live) {
             if constexpr (!COLSUM) {
                 // streamed rows are keys j, this lane's row is query i = srow: need j <= i.
                 // m_run tracks the maximum of the raw products (c2 > 0 keeps the order);
@@ -276,8 +332,9 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                 l_run = l_run * __builtin_amdgcn_exp2f((m_run - ms) * c2) + (sum0 + sum1);
                 m_run = mx;
             } else {
-                // streamed rows are queries i, this lane's row is key j = srow: need i >= j
-                const float *ll = lse_l + buf * BN;
+                // streamed rows are queries i, this lane's row is key j = srow: need
+                // j <= i < n
+                const float *ll = lse_l + lb * BN;
                 float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -288,11 +345,13 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                         float x[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            x[e] = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);       // rows past n: -inf
+                            x[e] = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);
                         if constexpr (MASKED) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (r0 + mb * 32 + 8 * gq + 4 * half + e < srow) x[e] = -INFINITY;
+                            for (int e = 0; e < 4; ++e) {
+                                const int i = r0 + mb * 32 + 8 * gq + 4 * half + e;
+                                if (i < srow || i >= n) x[e] = -INFINITY;
+                            }
                         }
                         sum0 += __builtin_amdgcn_exp2f(x[0]) + __builtin_amdgcn_exp2f(x[2]);
                         sum1 += __builtin_amdgcn_exp2f(x[1]) + __builtin_amdgcn_exp2f(x[3]);
@@ -300,22 +359,27 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                 c_run += sum0 + sum1;
             }
         }
-
-        if (more) stash(tile + 1, buf ^ 1);
-        dma_wait();
-        __syncthreads();
+        tb = tb == NTB - 1 ? 0 : tb + 1;
+        lb = (lb + 1) & (NLB - 1);
+        dma_wait_upto<CPF>();
+        wg_barrier();
     };
     // SROWS is a multiple of BN, so the tiles that touch the diagonal are exactly
     // those that overlap this workgroup's own rows [s0, s0 + SROWS)
-    static_assert(SROWS % BN == 0, "diagonal tiles are whole");
-    const int t_diag0 = s0 / BN, t_diag1 = min(t_end, (s0 + SROWS) / BN);
     if constexpr (!COLSUM) {
+        const int t_diag0 = s0 / BN;
         for (int tile = t_begin; tile < t_diag0; ++tile) tile_step(tile, std::false_type{});
         for (int tile = t_diag0; tile < t_end; ++tile) tile_step(tile, std::true_type{});
     } else {
+        const int t_diag1 = min(t_end, (s0 + SROWS) / BN);
+        // a ragged last tile holds rows past n: it takes the masking path as well
+        const int t_rag = (n % BN) ? max(t_diag1, t_end - 1) : t_end;
         for (int tile = t_begin; tile < t_diag1; ++tile) tile_step(tile, std::true_type{});
-        for (int tile = t_diag1; tile < t_end; ++tile) tile_step(tile, std::false_type{});
+        for (int tile = t_diag1; tile < t_rag; ++tile) tile_step(tile, std::false_type{});
+        for (int tile = t_rag; tile < t_end; ++tile) tile_step(tile, std::true_type{});
     }
+    if (grp == 0) wg_barrier();            // the barrier the second group spent at the start
+    dma_wait_upto<0>();                    // trailing repeat requests land before the LDS is released
 
     if constexpr (!COLSUM) {
         const float m2 = __shfl_xor(m_run, 32, 64), l2 = __shfl_xor(l_run, 32, 64);
@@ -329,7 +393,7 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     }
 }
 
-template <int DT, int D, int NWV, bool COLSUM>
+template <int DT, int D, bool COLSUM>
 hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
                        float *lse2, float *colsum, hipStream_t st)
 {
@@ -337,21 +401,27 @@ hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const
     constexpr int ES = DT == H2O_F32 ? 4 : 2;
     constexpr int MB = (D * ES >= 512) ? 1 : 2;      // keep the two tile buffers under 48 KiB
     constexpr int BN = 32 * MB;
-    constexpr size_t smem = 2 * (size_t)BN * (D * ES) + 2 * BN * sizeof(float);
-    static_assert(smem <= 48 * 1024, "tile buffers must fit the default LDS limit");
+    constexpr size_t smem = NTB * (size_t)BN * (D * ES) + NLB * BN * sizeof(float);
     const int heads = cfg.batch * cfg.heads;
     const int nblk = (n + SROWS - 1) / SROWS;
     const float c2 = (float)(scale * 1.4426950408889634);
-    hipLaunchKernelGGL((prefill_pass_kernel<DT, D, MB, NWV, COLSUM>),
+    auto kern = prefill_pass_kernel<DT, D, MB, COLSUM>;
+    if (smem > 48 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern,
                        dim3((unsigned)((heads + 63) / 64) * 64 * nblk),
                        dim3(NWV * 64), smem, st, static_cast<const char *>(Q),
                        static_cast<const char *>(K), n, heads, c2, lse2, colsum);
     return hipGetLastError();
 }
 
-#ifndef PREFILL_WAVES
-#define PREFILL_WAVES 8
-#endif
 template <bool COLSUM>
 hipError_t dispatch(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
                     float *lse2, float *colsum, hipStream_t st)
@@ -359,14 +429,14 @@ hipError_t dispatch(const h2o_config &cfg, double scale, const void *Q, const vo
     const int d = cfg.head_dim;
     switch (cfg.dtype) {
     case H2O_F32:
-        return d == 64 ? launch_pass<H2O_F32, 64, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_F32, 128, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_F32, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_F32, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
     case H2O_F16:
-        return d == 64 ? launch_pass<H2O_F16, 64, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_F16, 128, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_F16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_F16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
     default:
-        return d == 64 ? launch_pass<H2O_BF16, 64, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_BF16, 128, PREFILL_WAVES, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_BF16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
+                       : launch_pass<H2O_BF16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
     }
 }
 
