@@ -25,11 +25,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0       # dense bf16 / fp16 matrix peak of the part
 # HBM bytes per generation-step launch read back from the profiler's FETCH_SIZE /
 # WRITE_SIZE counters (each scaled by what the same counter reports for a plain
 # 256 MiB copy: x2.000 and x1.000), from the runs summarised under profiles/.
 # Counters cannot be collected inside a timed run, so the figure is carried here.
-PROFILED_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 111.2e6}
+PROFILED_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 111.1e6, "opt30b_layer_f16": 391.7e6,
+                          "stack32_f16": 888.4e6}
+# same for one launch pair of the prompt-scoring passes (read + written)
+PROFILED_PREFILL_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 1191.2e6, "prefill_bf16": 778.7e6,
+                                  "opt30b_layer_f16": 4227.1e6}
 
 
 def decode_bytes_per_head_step(k: int, d: int, esize: int) -> int:
@@ -38,6 +43,32 @@ def decode_bytes_per_head_step(k: int, d: int, esize: int) -> int:
     v_new read and the new K row, V row and output written (6 rows), plus the
     victim's score and position written (8 B)."""
     return 2 * k * d * esize + 12 * k + 6 * d * esize + 8
+
+
+def prefill_flops_per_pass(n: int, d: int, heads: int) -> int:
+    """Algorithmic flops of one masked QK^T over all heads: n(n+1)/2 visible
+    products per head, 2d flops each."""
+    return n * (n + 1) * d * heads
+
+
+def time_prefill_passes(hb, cfg, Q, K, n, ws, stream, reps=5):
+    """Average duration (ms) of the two matrix-core passes (row statistics +
+    column sums) launched back to back, HIP events on the launch stream."""
+    import torch
+    out = torch.empty((cfg.batch, cfg.heads, n), dtype=torch.float32, device=Q.device)
+    sp = stream.cuda_stream
+    hb.h2o_prefill_colsum(cfg, Q, K, n, ws, ws.numel(), out, sp)
+    stream.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = float("inf")
+    for _ in range(3):
+        e0.record(stream)
+        for _ in range(reps):
+            hb.h2o_prefill_colsum(cfg, Q, K, n, ws, ws.numel(), out, sp)
+        e1.record(stream)
+        stream.synchronize()
+        best = min(best, e0.elapsed_time(e1) / reps)
+    return best
 
 
 def cpu_baseline(w, sample_heads: int):
@@ -64,7 +95,8 @@ def cpu_baseline(w, sample_heads: int):
     dt = time.perf_counter() - t0
     heads = w.batch * w.heads
     whole = dt * heads / sample_heads                    # heads are independent and identical
-    return {"value": w.batch * w.steps / whole, "unit": "tokens/s", "cores": threads,
+    tokens = w.batch * (w.steps if w.steps else w.prompt)
+    return {"value": tokens / whole, "unit": "tokens/s", "cores": threads,
             "kind": "oracle",
             "sample": "%d of %d heads, full prompt phase + %d steps each, %.1f s measured, "
                       "scaled by head count" % (sample_heads, heads, w.steps, dt)}
@@ -79,6 +111,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = all)")
+    ap.add_argument("--decode-steps", type=int, default=0,
+                    help="profiling aid: run only this many generation steps per pass (0 = the "
+                         "workload's own count); the JSON line reports the count it ran")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (calibrates the profiler's "
                          "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
@@ -94,6 +129,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     B, Hh, d, n, T = w.batch, w.heads, w.head_dim, w.prompt, w.steps
+    if args.decode_steps > 0:
+        T = min(T, args.decode_steps)
     k = w.budget
     esize = 4 if w.dtype == torch.float32 else 2
 
@@ -182,9 +219,14 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
 
+        # the two matrix-core passes of the prompt phase on their own
+        pre_pass_ms = None
+        if L == 1:
+            pre_pass_ms = time_prefill_passes(hb, caches[0].cfg, Q, K, n, ws, stream)
+
         # generation-only timing in the same launch mode (graph of all step launches)
         dec_graph_us = None
-        if graph is not None:
+        if graph is not None and T > 0:
             g2 = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g2, stream=stream):
                 decode_all(stream.cuda_stream)
@@ -200,11 +242,21 @@ def main():
             dec_graph_us = e0.elapsed_time(e1) * 1e3 / (reps * T * L)
 
     ms_per_step = dt * 1e3 / args.steps
-    tokens_per_s = B * T / (dt / args.steps)
-    dec_us_eager = min(decode_ms) * 1e3 / (T * L)
-    dec_us = dec_graph_us if dec_graph_us is not None else dec_us_eager
-    bytes_per_launch = decode_bytes_per_head_step(k, d, esize) * B * Hh
-    achieved = bytes_per_launch / (dec_us * 1e-6) / 1e9
+    # generated tokens per second; a prompt-only workload counts prompt tokens
+    tokens_per_s = B * (T if T else n) / (dt / args.steps)
+    mfma_roofline = None
+    if pre_pass_ms is not None:
+        fl = 2 * prefill_flops_per_pass(n, d, B * Hh)
+        tf = fl / (pre_pass_ms * 1e-3) / 1e12
+        mfma_roofline = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf / MFMA_PEAK_TFLOPS, "traffic": PROFILED_PREFILL_TRAFFIC_BYTES.get(w.name),
+                         "kernel": "prefill_pass_kernel (row statistics + column sums, two launches)",
+                         "flops_per_launch_pair": fl, "ms_per_launch_pair": pre_pass_ms}
+    if T > 0:
+        dec_us_eager = min(decode_ms) * 1e3 / (T * L)
+        dec_us = dec_graph_us if dec_graph_us is not None else dec_us_eager
+        bytes_per_launch = decode_bytes_per_head_step(k, d, esize) * B * Hh
+        achieved = bytes_per_launch / (dec_us * 1e-6) / 1e9
     rec = {
         "metric": "H2O decode step: achieved HBM GB/s (% peak) + tokens/s, OPT-6.7B-shape layer",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -214,18 +266,25 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "heads": Hh, "head_dim": d, "prompt": n,
                    "decode_steps": T, "layers": L, "budget": k, "heavy": w.heavy, "recent": w.recent,
-                   "step": ("cache reset + prompt scoring/compression + %d generation steps" % T) if L == 1
+                   "step": ("cache reset + prompt scoring/compression" +
+                            (" + %d generation steps" % T if T else "")) if L == 1
                    else ("%d generation steps x %d resident layer caches (prompt phase done before "
                          "the clock starts)" % (T, L)),
                    "launch": "eager" if graph is None else "hip-graph replay"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": PROFILED_TRAFFIC_BYTES.get(w.name),
-                     "kernel": "decode_resident_kernel", "bytes_per_launch": bytes_per_launch,
-                     "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager},
-        "decode_tokens_per_s": B / (dec_us * L * 1e-6),
         "prefill_ms": min(prefill_ms) if L == 1 else None,
     }
+    if T > 0:
+        # the dominant kernel: the generation step, HBM-bound
+        rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": PROFILED_TRAFFIC_BYTES.get(w.name),
+                           "kernel": "decode_resident_kernel", "bytes_per_launch": bytes_per_launch,
+                           "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager}
+        rec["decode_tokens_per_s"] = B / (dec_us * L * 1e-6)
+        if mfma_roofline is not None:
+            rec["prefill_roofline"] = mfma_roofline
+    else:
+        rec["roofline"] = mfma_roofline
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
