@@ -137,6 +137,47 @@ int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K,
                        size_t ws_bytes, float *colsum_out, void *hip_stream);
 
 /*
+ * Device bytes of scratch h2o_prefill_attention / h2o_prefill_attention_scores
+ * need for a prompt of n tokens (a transposed copy of V padded to whole tiles,
+ * then the scratch of h2o_prefill_workspace_bytes).  Returns 0 for invalid
+ * arguments and for H2O_F32 (16-bit element types only).
+ */
+size_t h2o_prefill_attention_workspace_bytes(const h2o_config *cfg, int32_t n);
+
+/*
+ * Attention over the prompt (the prompt phase runs with the full cache, App. A
+ * generation commentary; exact process of App. D): for every head
+ *     out_i = sum_{j <= i} softmax_j(scale * <Q_i, K_j>) V_j,
+ * one flash-style MFMA kernel (online softmax, fp32 accumulation, the
+ * probabilities rounded to cfg->dtype for the second product).  The row
+ * log-sum-exps it produces are what the column-sum pass needs, so a layer that
+ * calls this gets the H2O scores for one extra matrix pass
+ * (h2o_prefill_attention_scores) instead of two.
+ *   Q, K, V   [batch, heads, n, head_dim] in cfg->dtype (H2O_F16 or H2O_BF16)
+ *   out       [batch, heads, n, head_dim] in cfg->dtype
+ *   lse_out   nullable, float [batch, heads, n]: log sum_j exp(scale * <Q_i, K_j>)
+ *   workspace >= h2o_prefill_attention_workspace_bytes(cfg, n)
+ * Needs no cache.  Errors: EINVAL, EUNSUPPORTED (H2O_F32, n > H2O_MAX_PROMPT),
+ * ENOMEM, EHIP.
+ */
+int h2o_prefill_attention(const h2o_config *cfg, const void *Q, const void *K,
+                          const void *V, int32_t n, void *workspace,
+                          size_t ws_bytes, void *out, float *lse_out,
+                          void *hip_stream);
+
+/*
+ * The whole prompt phase of an H2O attention layer: h2o_prefill_attention, the
+ * column sums of the same softmax matrix from its row statistics (Algorithm 2's
+ * accumulate line over the prompt rows), and h2o_prefill_select on the sums.
+ * `colsum_out` (nullable) additionally receives the column sums.  The cache
+ * must be empty.  Errors: those of the three calls.
+ */
+int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K,
+                                 const void *V, int32_t n, void *workspace,
+                                 size_t ws_bytes, void *out, float *colsum_out,
+                                 void *hip_stream);
+
+/*
  * One generation step for the token at position t, one fused kernel launch
  * (Definition 2.2, Algorithm 2, App. A decode commentary), per head:
  *   1. logits  s_j = scale * <q, K[slot j]> for every occupied slot, and

@@ -27,7 +27,8 @@ EXPORTS = (
     "h2o_cache_bytes", "h2o_prefill_workspace_bytes", "h2o_cache_init", "h2o_cache_reset",
     "h2o_cache_destroy", "h2o_prefill_colsum", "h2o_prefill_select", "h2o_prefill_scores",
     "h2o_decode_step", "h2o_cache_snapshot", "h2o_cache_restore", "h2o_cache_tokens_seen",
-    "h2o_cache_regions", "h2o_status_str",
+    "h2o_cache_regions", "h2o_status_str", "h2o_prefill_attention_workspace_bytes",
+    "h2o_prefill_attention", "h2o_prefill_attention_scores",
 )
 
 
@@ -61,6 +62,10 @@ _lib.h2o_cache_destroy.restype = None
 _lib.h2o_prefill_colsum.argtypes = [_cfgp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
 _lib.h2o_prefill_select.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp]
 _lib.h2o_prefill_scores.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
+_lib.h2o_prefill_attention_workspace_bytes.restype = _sz
+_lib.h2o_prefill_attention_workspace_bytes.argtypes = [_cfgp, _i32]
+_lib.h2o_prefill_attention.argtypes = [_cfgp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp, _vp]
+_lib.h2o_prefill_attention_scores.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp, _vp]
 _lib.h2o_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.h2o_cache_snapshot.argtypes = [_vp, _vp, _vp, _vp]
 _lib.h2o_cache_restore.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
@@ -142,6 +147,24 @@ def h2o_prefill_scores(cache, Q, K, V, n, workspace, ws_bytes, colsum_out=None, 
     _check(_lib.h2o_prefill_scores(cache, _ptr(Q), _ptr(K), _ptr(V), int(n), _ptr(workspace),
                                    int(ws_bytes), _ptr(colsum_out), _stream(stream)),
            "h2o_prefill_scores")
+
+
+def h2o_prefill_attention_workspace_bytes(cfg: h2o_config, n: int) -> int:
+    return int(_lib.h2o_prefill_attention_workspace_bytes(ctypes.byref(cfg), int(n)))
+
+
+def h2o_prefill_attention(cfg, Q, K, V, n, workspace, ws_bytes, out, lse_out=None, stream=None) -> None:
+    _check(_lib.h2o_prefill_attention(ctypes.byref(cfg), _ptr(Q), _ptr(K), _ptr(V), int(n),
+                                      _ptr(workspace), int(ws_bytes), _ptr(out), _ptr(lse_out),
+                                      _stream(stream)), "h2o_prefill_attention")
+
+
+def h2o_prefill_attention_scores(cache, Q, K, V, n, workspace, ws_bytes, out, colsum_out=None,
+                                 stream=None) -> None:
+    _check(_lib.h2o_prefill_attention_scores(cache, _ptr(Q), _ptr(K), _ptr(V), int(n),
+                                             _ptr(workspace), int(ws_bytes), _ptr(out),
+                                             _ptr(colsum_out), _stream(stream)),
+           "h2o_prefill_attention_scores")
 
 
 def h2o_decode_step(cache, q, k_new, v_new, out, stream=None) -> None:

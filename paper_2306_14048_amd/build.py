@@ -18,7 +18,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libh2o_hip.so")
 OBJ_DIR = os.path.join(PKG, "_build")
-SOURCES = ["h2o_api.hip", "decode_step.hip", "prefill_scores.hip", "select_gather.hip"]
+SOURCES = ["h2o_api.hip", "decode_step.hip", "prefill_scores.hip", "prefill_attention.hip",
+           "select_gather.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -144,6 +144,50 @@ int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K, const voi
     return h2o_prefill_select(cache, K, V, sums, n, hip_stream);
 }
 
+size_t h2o_prefill_attention_workspace_bytes(const h2o_config *cfg, int32_t n)
+{
+    if (check_config(cfg) != H2O_OK || n < 1 || n > H2O_MAX_PROMPT) return 0;
+    if (cfg->dtype == H2O_F32) return 0;
+    return align_up(h2o_attn_vt_bytes(*cfg, n), 256) + h2o_prefill_workspace_bytes(cfg, n);
+}
+
+int h2o_prefill_attention(const h2o_config *cfg, const void *Q, const void *K, const void *V,
+                          int32_t n, void *workspace, size_t ws_bytes, void *out, float *lse_out,
+                          void *hip_stream)
+{
+    const int rc = check_config(cfg);
+    if (rc != H2O_OK) return rc;
+    if (!Q || !K || !V || !workspace || !out || n < 1) return H2O_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(workspace) ||
+        !aligned16(out) || !aligned16(lse_out))
+        return H2O_EINVAL;
+    if (n > H2O_MAX_PROMPT || cfg->dtype == H2O_F32) return H2O_EUNSUPPORTED;
+    if (ws_bytes < h2o_prefill_attention_workspace_bytes(cfg, n)) return H2O_ENOMEM;
+    char *ws = static_cast<char *>(workspace);
+    float *lse2 = reinterpret_cast<float *>(ws + align_up(h2o_attn_vt_bytes(*cfg, n), 256));
+    return hip_rc(h2o_launch_prefill_attention(*cfg, h2o_scale_of(*cfg), Q, K, V, n, ws, lse2,
+                                               lse_out, out, static_cast<hipStream_t>(hip_stream)));
+}
+
+int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K, const void *V,
+                                 int32_t n, void *workspace, size_t ws_bytes, void *out,
+                                 float *colsum_out, void *hip_stream)
+{
+    if (!cache || !aligned16(colsum_out)) return H2O_EINVAL;
+    if (cache->t != 0) return H2O_ESTATE;
+    const h2o_config *cfg = &cache->cfg;
+    int rc = h2o_prefill_attention(cfg, Q, K, V, n, workspace, ws_bytes, out, nullptr, hip_stream);
+    if (rc != H2O_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    const size_t half = h2o_prefill_workspace_bytes(cfg, n) / 2;
+    float *lse2 = reinterpret_cast<float *>(ws + align_up(h2o_attn_vt_bytes(*cfg, n), 256));
+    float *sums = colsum_out ? colsum_out : reinterpret_cast<float *>(reinterpret_cast<char *>(lse2) + half);
+    const hipError_t e = h2o_launch_prefill_colsum(*cfg, h2o_scale_of(*cfg), Q, K, n, lse2, sums, st);
+    if (e != hipSuccess) return H2O_EHIP;
+    return h2o_prefill_select(cache, K, V, sums, n, hip_stream);
+}
+
 int h2o_decode_step(h2o_cache *cache, const void *q, const void *k_new, const void *v_new,
                     void *out, void *hip_stream)
 {

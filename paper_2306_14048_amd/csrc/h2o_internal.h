@@ -33,6 +33,13 @@ hipError_t h2o_launch_prefill_lse(const h2o_config &cfg, double scale, const voi
 hipError_t h2o_launch_prefill_colsum(const h2o_config &cfg, double scale, const void *Q,
                                      const void *K, int n, const float *lse, float *colsum,
                                      hipStream_t st);
+// causal attention over the prompt: V is transposed into `vt` (h2o_attn_vt_bytes
+// bytes), `lse2` receives log2 of every row's normaliser of exp2(scale*log2(e)*<q,k>),
+// `lse_nat` (nullable) the natural-log row log-sum-exp; 16-bit element types only
+size_t h2o_attn_vt_bytes(const h2o_config &cfg, int n);
+hipError_t h2o_launch_prefill_attention(const h2o_config &cfg, double scale, const void *Q,
+                                        const void *K, const void *V, int n, void *vt,
+                                        float *lse2, float *lse_nat, void *out, hipStream_t st);
 hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const void *V,
                                     const float *score, int n, hipStream_t st);
 

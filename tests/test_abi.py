@@ -48,6 +48,10 @@ def test_size_queries_and_validation(hb):
         assert hb.h2o_cache_bytes(c) == 0
     assert hb.h2o_prefill_workspace_bytes(ok, 0) == 0
     assert hb.h2o_prefill_workspace_bytes(ok, hb.H2O_MAX_PROMPT + 1) == 0
+    # transposed V padded to whole 64-key tiles, then the scoring scratch
+    assert hb.h2o_prefill_attention_workspace_bytes(ok, 2000) == \
+        16 * 32 * 128 * 2048 * 2 + hb.h2o_prefill_workspace_bytes(ok, 2000)
+    assert hb.h2o_prefill_attention_workspace_bytes(ok, 0) == 0
 
 
 def test_error_codes_without_device(hb):
@@ -68,6 +72,15 @@ def test_error_codes_without_device(hb):
     assert lib.h2o_prefill_colsum(ctypes.byref(ok), 0x1000, 0x1000, 8, 0x1000, 8, 0x1000, None) == hb.H2O_ENOMEM
     assert lib.h2o_prefill_colsum(ctypes.byref(ok), 0x1000, 0x1000, hb.H2O_MAX_PROMPT + 1, 0x1000,
                                   1 << 30, 0x1000, None) == hb.H2O_EUNSUPPORTED
+    assert lib.h2o_prefill_attention(ctypes.byref(ok), 0x1000, 0x1000, None, 8, 0x1000, 1 << 20, 0x1000,
+                                     None, None) == hb.H2O_EINVAL
+    assert lib.h2o_prefill_attention(ctypes.byref(ok), 0x1000, 0x1000, 0x1000, 8, 0x1000, 8, 0x1000,
+                                     None, None) == hb.H2O_ENOMEM
+    f32 = hb.make_config(1, 1, 128, 4, 4, hb.H2O_F32)
+    assert lib.h2o_prefill_attention(ctypes.byref(f32), 0x1000, 0x1000, 0x1000, 8, 0x1000, 1 << 20,
+                                     0x1000, None, None) == hb.H2O_EUNSUPPORTED
+    assert lib.h2o_prefill_attention_scores(None, 0x1000, 0x1000, 0x1000, 8, 0x1000, 1 << 20, 0x1000,
+                                            None, None) == hb.H2O_EINVAL
     lib.h2o_cache_destroy(None)
     assert hb.h2o_status_str(0) == "ok"
     assert "unsupported" in hb.h2o_status_str(hb.H2O_EUNSUPPORTED)
