@@ -71,6 +71,25 @@ def time_prefill_passes(hb, cfg, Q, K, n, ws, stream, reps=5):
     return best
 
 
+def time_attention(hb, cfg, Q, K, V, n, ws, out, stream, reps=5):
+    """Average duration (ms) of the prompt attention (transpose of V + the
+    attention kernel), HIP events on the launch stream."""
+    import torch
+    sp = stream.cuda_stream
+    hb.h2o_prefill_attention(cfg, Q, K, V, n, ws, ws.numel(), out, None, sp)
+    stream.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = float("inf")
+    for _ in range(3):
+        e0.record(stream)
+        for _ in range(reps):
+            hb.h2o_prefill_attention(cfg, Q, K, V, n, ws, ws.numel(), out, None, sp)
+        e1.record(stream)
+        stream.synchronize()
+        best = min(best, e0.elapsed_time(e1) / reps)
+    return best
+
+
 def cpu_baseline(w, sample_heads: int):
     """The oracle as it stands on this host's cores: prompt phase + all generation
     steps for `sample_heads` heads of the workload, threads over heads."""
@@ -111,6 +130,10 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = all)")
+    ap.add_argument("--prompt", choices=("scores", "attention"), default="scores",
+                    help="prompt phase: 'scores' = row statistics + column sums + compression (the "
+                         "default step); 'attention' = causal attention output whose row statistics "
+                         "feed the column sums, + compression (a layer's whole prompt phase)")
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="profiling aid: run only this many generation steps per pass (0 = the "
                          "workload's own count); the JSON line reports the count it ran")
@@ -141,6 +164,11 @@ def main():
         Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev)
         cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
         ws = cache.workspace(n)
+        attn_out = None
+        if args.prompt == "attention":
+            ws = torch.empty(hb.h2o_prefill_attention_workspace_bytes(cache.cfg, n),
+                             dtype=torch.uint8, device=dev)
+            attn_out = torch.empty_like(Q)
         Qp, Kp, Vp, wsp, wsn = Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel()
         caches.append(cache)
     else:
@@ -176,7 +204,10 @@ def main():
             hb.h2o_cache_reset(ptrs[0][0], sp)
         if timed_events:
             ev[0].record(stream)
-        if L == 1:
+        if L == 1 and args.prompt == "attention":
+            hb.h2o_prefill_attention_scores(ptrs[0][0], Qp, Kp, Vp, n, wsp, wsn, attn_out.data_ptr(),
+                                            None, sp)
+        elif L == 1:
             hb.h2o_prefill_scores(ptrs[0][0], Qp, Kp, Vp, n, wsp, wsn, None, sp)
         if timed_events:
             ev[1].record(stream)
@@ -220,9 +251,11 @@ def main():
         dt = time.perf_counter() - t0
 
         # the two matrix-core passes of the prompt phase on their own
-        pre_pass_ms = None
+        pre_pass_ms = attn_ms = None
         if L == 1:
             pre_pass_ms = time_prefill_passes(hb, caches[0].cfg, Q, K, n, ws, stream)
+        if L == 1 and args.prompt == "attention":
+            attn_ms = time_attention(hb, caches[0].cfg, Q, K, V, n, ws, attn_out, stream)
 
         # generation-only timing in the same launch mode (graph of all step launches)
         dec_graph_us = None
@@ -273,6 +306,15 @@ def main():
                    "launch": "eager" if graph is None else "hip-graph replay"},
         "prefill_ms": min(prefill_ms) if L == 1 else None,
     }
+    if attn_ms is not None:
+        # QK^T and PV over the visible half: twice the flops of one scoring pass
+        fl = 2 * prefill_flops_per_pass(n, d, B * Hh)
+        tf = fl / (attn_ms * 1e-3) / 1e12
+        rec["attention_roofline"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS,
+                                     "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS, "traffic": None,
+                                     "kernel": "transpose_v_kernel + prefill_attn_kernel",
+                                     "flops_per_launch": fl, "ms_per_launch": attn_ms}
+        rec["config"]["prompt_phase"] = "attention output + column sums + compression"
     if T > 0:
         # the dominant kernel: the generation step, HBM-bound
         rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

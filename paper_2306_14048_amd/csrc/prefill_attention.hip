@@ -286,27 +286,45 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
         const bool live = !LAST && (!MASKED || r0 <= w0 + 31);
         f32x16 sacc[MB];
         __builtin_amdgcn_s_setprio(2);
+        // Only one wave per SIMD is in its matrix phase, so nothing else hides the
+        // LDS latency of its operand reads: they run PF fragments ahead of the
+        // MFMAs that use them (a ring of PF registers quadruples).
+        constexpr int PF = 4;
         if (live_prev) {
+            constexpr int N = KS * NDB;
+            uint4 ring[PF];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
+            for (int i = 0; i < PF; ++i)
+                ring[i] = *reinterpret_cast<const uint4 *>(sb + va[i % NDB][i / NDB]);
 #pragma unroll
-                for (int db = 0; db < NDB; ++db) {
-                    const uint4 a = *reinterpret_cast<const uint4 *>(sb + va[db][ks]);
-                    oacc[db] = mma16<DT>(a, pfrag[ks], oacc[db]);
-                }
+            for (int i = 0; i < N; ++i) {
+                const int ks = i / NDB, db = i % NDB;
+                __builtin_amdgcn_sched_barrier(0);      // keep the reads PF ahead (the scheduler would pull them back)
+                oacc[db] = mma16<DT>(ring[i % PF], pfrag[ks], oacc[db]);
+                if (i + PF < N)
+                    ring[i % PF] = *reinterpret_cast<const uint4 *>(sb + va[(i + PF) % NDB][(i + PF) / NDB]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (live) {
+            constexpr int N = NF * MB;
+            uint4 ring[PF];
+#pragma unroll
+            for (int i = 0; i < PF; ++i)
+                ring[i] = *reinterpret_cast<const uint4 *>(sb + ka[i / MB][i % MB]);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sacc[mb][v] = 0.f;
 #pragma unroll
-            for (int f = 0; f < NF; ++f)
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const uint4 a = *reinterpret_cast<const uint4 *>(sb + ka[f][mb]);
-                    sacc[mb] = mma16<DT>(a, st[f], sacc[mb]);
-                }
+            for (int i = 0; i < N; ++i) {
+                const int f = i / MB, mb = i % MB;
+                __builtin_amdgcn_sched_barrier(0);
+                sacc[mb] = mma16<DT>(ring[i % PF], st[f], sacc[mb]);
+                if (i + PF < N)
+                    ring[i % PF] = *reinterpret_cast<const uint4 *>(sb + ka[(i + PF) / MB][(i + PF) % MB]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_s_setprio(0);
         dma_wait_upto<CPF>();
@@ -330,12 +348,18 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
             mx = fmaxf(mx, other_half(mx));              // both halves of a query use one reference
             // mx is finite from the first tile on: key 0 is visible to every query
             if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {      // rescale only when a maximum moved
-                const float alpha = __builtin_amdgcn_exp2f((m_run - mx) * c2);   // 0 on the first tile
+                float alpha = __builtin_amdgcn_exp2f((m_run - mx) * c2);         // 0 on the first tile
                 l_run *= alpha;
+                // in place (written as an instruction so that the branch leaves the
+                // accumulator in the registers it already occupies).  The compiler does
+                // not see what an asm statement reads, so the wait states a consumer of
+                // a transcendental result needs are spelled out here.
+                asm volatile("s_nop 4" : "+v"(alpha));
 #pragma unroll
                 for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+                    for (int v = 0; v < 16; ++v)
+                        asm volatile("v_mul_f32 %0, %0, %1" : "+v"(oacc[db][v]) : "v"(alpha));
                 m_run = mx;
             }
             const float nms = -m_run * c2;
