@@ -27,6 +27,7 @@
 // reproducible against an fp64 reference; the kernel is HBM-bound and the extra
 // ALU work hides behind the stream.  P.V is accumulated in fp32.
 #include "h2o_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -45,6 +46,39 @@ __device__ inline uint4 load_stream(const char *p)
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
     return make_uint4(t.x, t.y, t.z, t.w);
+}
+
+// Marks the point from which a loaded row may be unpacked: inside a loop the
+// compiler otherwise moves the unpacking of 16-bit pairs to the end of the
+// previous iteration, right behind the loads, and with it the wait for them.
+__device__ inline void pin(uint4 &v)
+{
+    asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+}
+
+// The elements of a loaded 16-byte piece as floats, taken from its four 32-bit
+// words with integer operations (a 16-bit element view of the registers makes the
+// compiler carry every half in a register of its own across loop iterations).
+template <int DT>
+__device__ inline void piece_to_float(const uint4 &v, float (&f)[Elem<DT>::EPL])
+{
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+    if constexpr (DT == H2O_F32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(w[i]);
+    } else if constexpr (DT == H2O_F16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = (float)__builtin_bit_cast(_Float16, (unsigned short)(w[i] & 0xffffu));
+            f[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(w[i] >> 16));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
 }
 
 // ---- DPP helpers (row = 16 lanes) ---------------------------------------------
@@ -86,17 +120,6 @@ __device__ inline double row_max(double a)
     a = fmax(a, dpp<DPP_HALF_MIRROR>(a));
     return fmax(a, dpp<DPP_MIRROR>(a));
 }
-__device__ inline unsigned long long umin64(unsigned long long a, unsigned long long b)
-{
-    return a < b ? a : b;
-}
-__device__ inline unsigned long long row_min(unsigned long long a)
-{
-    a = umin64(a, dpp<DPP_XOR1>(a));
-    a = umin64(a, dpp<DPP_XOR2>(a));
-    a = umin64(a, dpp<DPP_HALF_MIRROR>(a));
-    return umin64(a, dpp<DPP_MIRROR>(a));
-}
 // value of lane L of the wave, as a wave-uniform scalar
 __device__ inline double lane_value(double v, int L)
 {
@@ -127,12 +150,6 @@ __device__ inline double wave_sum(double v)
     v = group_sum<16>(v);
     return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
-__device__ inline unsigned long long wave_min(unsigned long long v)
-{
-    v = row_min(v);
-    return umin64(umin64(lane_value(v, 0), lane_value(v, 16)),
-                  umin64(lane_value(v, 32), lane_value(v, 48)));
-}
 constexpr unsigned long long NO_CANDIDATE = ~0ull;
 
 // ---- pieces shared by the two kernels -------------------------------------------
@@ -150,40 +167,6 @@ __device__ inline void wave_output_to_lds(float (&o)[EPL], float *o_l, int wave,
     if (sub == 0) {
 #pragma unroll
         for (int i = 0; i < EPL; ++i) o_l[wave * D + li * EPL + i] = o[i];
-    }
-}
-
-// Final writes of a step: the output row, and the new token into slot `target`
-// (K row, V row, first score, position); target < 0 = the token is not kept.
-template <int DT, int D, int NW>
-__device__ inline void write_back(const float *o_l, float p_self, int target, int t, size_t hoff,
-                                  int head, char *Kb, char *Vb, float *acc_g, int32_t *pos_g,
-                                  const typename Elem<DT>::T *knh, const typename Elem<DT>::T *vnh,
-                                  char *out_g)
-{
-    using E = Elem<DT>;
-    using T = typename E::T;
-    constexpr int EPL = E::EPL, LPR = D / EPL;
-    constexpr unsigned ROWB = D * sizeof(T);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < D) {
-        float r = p_self * E::to_f(vnh[tid]);
-#pragma unroll
-        for (int w = 0; w < NW; ++w) r += o_l[w * D + tid];
-        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r);
-    }
-    if (target >= 0) {
-        if (tid == 0) { pos_g[hoff + target] = t; acc_g[hoff + target] = p_self; }
-        if (wave == NW - 1) {            // a wave that is not busy with the output row
-            if (lane < LPR) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(knh + lane * EPL);
-                *reinterpret_cast<uint4 *>(Kb + (size_t)target * ROWB + lane * 16) = v;
-            } else if (lane < 2 * LPR) {
-                const int l2 = lane - LPR;
-                const uint4 v = *reinterpret_cast<const uint4 *>(vnh + l2 * EPL);
-                *reinterpret_cast<uint4 *>(Vb + (size_t)target * ROWB + l2 * 16) = v;
-            }
-        }
     }
 }
 
@@ -415,44 +398,59 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     }
 }
 
-// ---- streaming kernel: any budget up to H2O_MAX_BUDGET --------------------------------
+// ---- chunked kernel: any budget up to H2O_MAX_BUDGET ----------------------------------
 //
-// The key rounds followed by the value rounds form one stream pulled through a
-// ring of U register buffers per wave: a buffer is refilled with the entry U
-// places ahead as soon as it has been consumed.  Logits, probabilities and the
-// per-slot bookkeeping live in LDS; thread j % NT handles slot j.
+// The same straight-line body as the register-resident kernel, run over the
+// head in chunks of U rounds (CH = U * RPI slots).  The chunks' key rounds
+// followed by their value rounds form one stream through the ring of U
+// register buffers: the buffer of round u of a chunk is refilled with round u
+// of the next chunk (after the last key chunk: of the first value chunk) as
+// soon as it has been consumed, so the ring stays full across chunk borders
+// and across the softmax barrier.  No load is conditional (addresses are
+// clamped to the last occupied row); the last value chunk, which has nothing
+// left to request, is a second copy of the body without refills.
+//
+// A wave owns the slots whose rows it reads, per chunk one per lane; the fp64
+// logits of all chunks are kept in a wave-private LDS array (8 bytes per slot),
+// from which the exponentials are evaluated twice: once for the normaliser
+// (key phase) and once for the probabilities (value phase; the normaliser is
+// only known after the last key chunk).  Scores and positions are read one
+// chunk ahead of their use.  Softmax shift and overflow fallback as above.
 template <int DT, int D, int NW, int U>
-__global__ __launch_bounds__(NW * 64, 4) void decode_stream_kernel(
+__global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
-    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale)
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int chunks)
 {
     using E = Elem<DT>;
     using T = typename E::T;
     constexpr int EPL = E::EPL;
     constexpr int LPR = D / EPL;
     constexpr int RPW = 64 / LPR;
-    constexpr int NT = NW * 64;
     constexpr int RPI = NW * RPW;
+    constexpr int OWN = U * RPW;
+    constexpr int CH = U * RPI;          // slots per chunk
+    constexpr int PITCH = LPR + 1;
     constexpr unsigned ROWB = D * sizeof(T);
     static_assert(LPR >= 8 && LPR <= 32, "a row is read by 8, 16 or 32 lanes");
+    static_assert(OWN <= 64, "one slot per lane and chunk");
 
     const int head = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane / LPR, li = lane % LPR;
-    const int kp = (k + 2) & ~1;         // keeps the arrays 8-byte aligned
 
     extern __shared__ __align__(16) unsigned char smem[];
-    double *s_l = reinterpret_cast<double *>(smem);            // [kp] logits, then exp
-    float *p_l = reinterpret_cast<float *>(s_l + kp);          // [kp] probabilities
-    float *acc_l = p_l + kp;                                   // [kp] updated scores
-    int *pos_l = reinterpret_cast<int *>(acc_l + kp);          // [kp]
-    float *o_l = reinterpret_cast<float *>(pos_l + kp);        // [NW][D]
-    double *red_max = reinterpret_cast<double *>(o_l + NW * D);
-    double *red_sum = red_max + NW;
-    unsigned long long *red_key = reinterpret_cast<unsigned long long *>(red_sum + NW);
-    int *target_l = reinterpret_cast<int *>(red_key + NW);     // [1]
+    double *part_l = reinterpret_cast<double *>(smem);                 // [NW][OWN][PITCH]
+    double *s_l = part_l + NW * OWN * PITCH;                           // [NW][chunks][OWN] logits
+    double *red_sum = s_l + (size_t)NW * chunks * OWN;                 // [NW]
+    double *red_max = red_sum + NW;                                    // [NW]
+    double *red_key = red_max + NW;                                    // [NW]
+    float *p_l = reinterpret_cast<float *>(red_key + NW);              // [NW][OWN]
+    float *o_l = p_l + NW * OWN;                                       // [NW][D]
+    double *part_w = part_l + wave * OWN * PITCH;
+    double *s_w = s_l + (size_t)wave * chunks * OWN;
+    float *p_w = p_l + wave * OWN;
 
     const size_t hoff = (size_t)head * k;
     char *Kb = Kc + hoff * ROWB;
@@ -461,22 +459,25 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_stream_kernel(
     const T *knh = reinterpret_cast<const T *>(kn_g) + (size_t)head * D;
     const T *vnh = reinterpret_cast<const T *>(vn_g) + (size_t)head * D;
 
-    const int rounds = (n_occ + RPI - 1) / RPI;
-    const int row0 = wave * RPW + sub;
-    const int vbase = (rounds + U - 1) / U * U;   // stream index of value round 0
-    // stream entry e: key round e for e < rounds, value round e - vbase for
-    // vbase <= e < vbase + rounds, nothing in between; entry e lives in buf[e % U]
-    auto load_row = [&](const char *base, int round) -> uint4 {
-        const unsigned rc = (unsigned)min(round * RPI + row0, max(n_occ, 1) - 1);   // in bounds
-        return load_stream(base + (rc * ROWB + (unsigned)li * 16u));
-    };
+    const int row0 = wave * RPW + sub;   // this lane's row inside a round
+    const int last = n_occ - 1;          // n_occ > CH >= 1 here
+    // slot this lane owns inside a chunk: the row its lane group reads in round lane / RPW
+    const int my_sc = (lane / RPW) * RPI + wave * RPW + (lane % RPW);
 
     const uint4 qraw = *reinterpret_cast<const uint4 *>(qh + li * EPL);
     const uint4 kraw = *reinterpret_cast<const uint4 *>(knh + li * EPL);
+    const uint4 vraw = *reinterpret_cast<const uint4 *>(vnh + li * EPL);
+    // byte offset of this lane's piece of round u of chunk c (clamped, in bounds)
+    auto row_off = [&](int c, int u) -> unsigned {
+        return (unsigned)min(c * CH + u * RPI + row0, last) * ROWB + (unsigned)li * 16u;
+    };
     uint4 buf[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-        if (u < rounds) buf[u] = load_row(Kb, u);
+    for (int u = 0; u < U; ++u) buf[u] = load_stream(Kb + row_off(0, u));
+    // bookkeeping of the slot owned in chunk 0 (requested behind the first key rounds)
+    int pos_nx = pos_g[hoff + min(my_sc, last)];
+    float acc_nx = acc_g[hoff + min(my_sc, last)];
+    __builtin_amdgcn_sched_barrier(0);
 
     double qd[EPL];
     double s_self;
@@ -492,58 +493,48 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_stream_kernel(
         s_self = group_sum<LPR>(a) * scale;
     }
 
-    // ---- logits ---------------------------------------------------------------
-    double m_run = s_self;               // running maximum (the softmax shift)
-    for (int r = 0; r < rounds; r += U) {
+    // ---- key phase -----------------------------------------------------------------
+    double m_loc = -INFINITY;
+    for (int c = 0; c < chunks; ++c) {
+        // what refills the ring: the next key chunk, or the first value chunk
+        const bool more_keys = c + 1 < chunks;
+        const char *nbase = more_keys ? Kb : Vb;
+        const int nc = more_keys ? c + 1 : 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int e = r + u;
-            if (e < rounds) {
-                const T *x = reinterpret_cast<const T *>(&buf[u]);
-                double a = 0.0;
+            pin(buf[u]);
+            float x[EPL];
+            piece_to_float<DT>(buf[u], x);
+            double a0 = 0.0, a1 = 0.0;
 #pragma unroll
-                for (int i = 0; i < EPL; ++i) a = fma((double)E::to_f(x[i]), qd[i], a);
-                const int nx = e + U;
-                if (nx < rounds) buf[u] = load_row(Kb, nx);
-                else if (nx >= vbase && nx - vbase < rounds) buf[u] = load_row(Vb, nx - vbase);
-                a = group_sum<LPR>(a) * scale;
-                const int row = e * RPI + row0;
-                if (li == 0 && row < n_occ) s_l[row] = a;
-                m_run = fmax(m_run, a);          // clamped duplicates repeat a real row
+            for (int i = 0; i < EPL; i += 2) {
+                a0 = fma((double)x[i], qd[i], a0);
+                a1 = fma((double)x[i + 1], qd[i + 1], a1);
             }
+            buf[u] = load_stream(nbase + row_off(nc, u));
+            part_w[(u * RPW + sub) * PITCH + li] = a0 + a1;
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
-    {
-        // value rounds the ring has not requested yet (the ring positions that
-        // held no entry between the last key round and value round 0)
-        const int primed = rounds + U - vbase;
+        __builtin_amdgcn_wave_barrier();
+        if (lane < OWN) {
+            const double *pr = part_w + lane * PITCH;
+            double a = pr[0], b2 = pr[1];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (u >= primed && u < rounds) buf[u] = load_row(Vb, u);
+            for (int i = 2; i < LPR; i += 2) { a += pr[i]; b2 += pr[i + 1]; }
+            const double s_j = (a + b2) * scale;
+            s_w[c * OWN + lane] = s_j;
+            if (c * CH + my_sc < n_occ) m_loc = fmax(m_loc, s_j);
+        }
+        __builtin_amdgcn_wave_barrier();     // the partial-sum tile is reused by the next chunk
     }
-    {
-        const double mw = wave_max(m_run);
-        if (lane == 0) red_max[wave] = mw;
-    }
-    for (int j = tid; j < n_occ; j += NT) {
-        pos_l[j] = pos_g[hoff + j];
-        acc_l[j] = acc_g[hoff + j];
-    }
-    lds_barrier();
 
-    // ---- exact softmax (slot j is always handled by thread j % NT, so pos_l /
-    // acc_l entries are only ever touched by the thread that wrote them) --------
-    double mx = red_max[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) mx = fmax(mx, red_max[w]);
+    // ---- normaliser (shift = the token's own logit; true maximum on overflow) --------
+    // (the exponentials are summed here, not in the key loop: q is no longer live)
+    double shift = s_self, e_self = 1.0;
     double d_loc = 0.0;
-    for (int j = tid; j < n_occ; j += NT) {
-        const double e = exp(s_l[j] - mx);
-        s_l[j] = e;
-        d_loc += e;
-    }
-    const double e_self = exp(s_self - mx);
+    if (lane < OWN)
+        for (int c = 0; c < chunks; ++c)
+            if (c * CH + my_sc < n_occ) d_loc += exp(s_w[c * OWN + lane] - shift);
     {
         const double dw = wave_sum(d_loc);
         if (lane == 0) red_sum[wave] = dw;
@@ -552,68 +543,118 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_stream_kernel(
     double den = e_self;
 #pragma unroll
     for (int w = 0; w < NW; ++w) den += red_sum[w];
+    if (!(den <= 1.79769313486231570815e+308)) {
+        const double mw = wave_max(m_loc);
+        if (lane == 0) red_max[wave] = mw;
+        lds_barrier();
+        shift = s_self;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) shift = fmax(shift, red_max[w]);
+        d_loc = 0.0;
+        if (lane < OWN)
+            for (int c = 0; c < chunks; ++c)
+                if (c * CH + my_sc < n_occ) d_loc += exp(s_w[c * OWN + lane] - shift);
+        e_self = exp(s_self - shift);
+        const double dw = wave_sum(d_loc);
+        if (lane == 0) red_sum[wave] = dw;
+        lds_barrier();
+        den = e_self;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) den += red_sum[w];
+    }
     const float p_self = (float)(e_self / den);
 
-    // ---- score update and eviction candidates ---------------------------------
-    unsigned long long key = NO_CANDIDATE;
-    const int last_cand = t - recent;    // window after this step = {t-R+1 .. t}
-    for (int j = tid; j < n_occ; j += NT) {
-        const float p = (float)(s_l[j] / den);
-        p_l[j] = p;
-        const float a = acc_l[j] + p;                     // binary32 accumulate
-        acc_l[j] = a;
-        const int pj = pos_l[j];
-        if (pj <= last_cand)
-            key = umin64(key, ((unsigned long long)__float_as_uint(a) << 32) | (unsigned)pj);
-    }
-    {
-        const unsigned long long kw = wave_min(key);
-        if (lane == 0) red_key[wave] = kw;
-        if (tid == 0) *target_l = n_occ < k ? n_occ : -1;
-    }
-    lds_barrier();
-    if (n_occ >= k) {
-        key = red_key[0];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) key = umin64(key, red_key[w]);
-        const unsigned long long self_key =
-            ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
-        if (key != NO_CANDIDATE && (recent != 0 || key < self_key)) {
-            const int wpos = (int)(unsigned)(key & 0xffffffffu);
-            for (int j = tid; j < n_occ; j += NT)
-                if (pos_l[j] == wpos) *target_l = j;      // positions are unique
-        }
-    }
-
-    // ---- output ---------------------------------------------------------------
+    // ---- value phase -----------------------------------------------------------------
     float o[EPL];
+    {
+        const float ps = (wave == 0 && sub == 0) ? p_self : 0.f;
+        const T *x = reinterpret_cast<const T *>(&vraw);
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) o[i] = 0.f;
-    for (int r = 0; r < rounds; r += U) {
+        for (int i = 0; i < EPL; ++i) o[i] = ps * E::to_f(x[i]);
+    }
+    unsigned long long best = NO_CANDIDATE;  // smallest (score, position) among this lane's slots
+    int best_slot = 0;
+    auto value_chunk = [&](int c, auto refill_tag) {
+        constexpr bool REFILL = decltype(refill_tag)::value;
+        const int slot = c * CH + my_sc;
+        const bool owner = lane < OWN && slot < n_occ;
+        const int pos_j = pos_nx;
+        float acc_j = acc_nx;
+        if (REFILL) {                        // the next chunk's bookkeeping, one chunk ahead
+            pos_nx = pos_g[hoff + min(slot + CH, last)];
+            acc_nx = acc_g[hoff + min(slot + CH, last)];
+        }
+        const double e_j = owner ? exp(s_w[c * OWN + min(lane, OWN - 1)] - shift) : 0.0;
+        const float p_j = (float)(e_j / den);
+        acc_j += p_j;                                            // binary32 accumulate
+        if (lane < OWN) p_w[lane] = p_j;
+        if (owner) {
+            acc_g[hoff + slot] = acc_j;
+            if (pos_j <= t - recent) {                           // window after this step = {t-R+1..t}
+                const unsigned long long key =
+                    ((unsigned long long)__float_as_uint(acc_j) << 32) | (unsigned)pos_j;
+                if (key < best) { best = key; best_slot = slot; }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int vr = r + u;
-            if (vr < rounds) {
-                const int row = vr * RPI + row0;
-                const float p = row < n_occ ? p_l[row] : 0.f;   // clamped duplicates add nothing
-                const uint4 raw = buf[u];
-                const int nx = vr + U;
-                if (nx < rounds) buf[u] = load_row(Vb, nx);
-                const T *x = reinterpret_cast<const T *>(&raw);
+            const float p = p_w[u * RPW + sub];
+            pin(buf[u]);
+            float x[EPL];
+            piece_to_float<DT>(buf[u], x);
 #pragma unroll
-                for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, E::to_f(x[i]), o[i]);
-            }
+            for (int i = 0; i < EPL; ++i) o[i] = fmaf(p, x[i], o[i]);
+            __builtin_amdgcn_sched_barrier(0);   // the row is consumed before its buffer is requested again
+            if (REFILL) buf[u] = load_stream(Vb + row_off(c + 1, u));
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
+        __builtin_amdgcn_wave_barrier();     // the probability row is reused by the next chunk
+    };
+    for (int c = 0; c + 1 < chunks; ++c) value_chunk(c, std::true_type{});
+    value_chunk(chunks - 1, std::false_type{});
     wave_output_to_lds<EPL, LPR, D>(o, o_l, wave, sub, li);
+    {
+        const double kw = wave_min_f64(__longlong_as_double((long long)best));
+        if (lane == 0) red_key[wave] = kw;
+    }
     lds_barrier();
 
-    // ---- write-back -----------------------------------------------------------
-    const int target = *target_l;
-    for (int j = tid; j < n_occ; j += NT)
-        if (j != target) acc_g[hoff + j] = acc_l[j];
-    write_back<DT, D, NW>(o_l, p_self, target, t, hoff, head, Kb, Vb, acc_g, pos_g, knh, vnh, out_g);
+    // ---- write-back -----------------------------------------------------------------
+    if (tid < D) {
+        float r = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) r += o_l[w * D + tid];
+        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r);
+    }
+    int tslot = -1;          // wave-uniform: the slot this wave has to fill, if any
+    if (n_occ < k) {
+        if (wave == 0) tslot = n_occ;
+    } else {
+        double wd = red_key[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) wd = fmin(wd, red_key[w]);
+        const unsigned long long win = (unsigned long long)__double_as_longlong(wd);
+        const unsigned long long self_key =
+            ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
+        const bool evict = wd == wd && (recent != 0 || win < self_key);
+        // keys are unique (positions are); the lane that holds the winner also wrote
+        // that slot's score above, so its stores below are ordered behind that one
+        const unsigned long long b = __ballot(evict && best == win);
+        if (b != 0) tslot = __builtin_amdgcn_readlane(best_slot, __ffsll((long long)b) - 1);
+    }
+    if (tslot >= 0) {
+        if (n_occ < k) {
+            if (lane == 0) { pos_g[hoff + tslot] = t; acc_g[hoff + tslot] = p_self; }
+        } else if (best_slot == tslot && best != NO_CANDIDATE) {
+            pos_g[hoff + tslot] = t;
+            acc_g[hoff + tslot] = p_self;
+        }
+        if (lane < LPR)
+            *reinterpret_cast<uint4 *>(Kb + (size_t)tslot * ROWB + li * 16) = kraw;
+        else if (lane < 2 * LPR)
+            *reinterpret_cast<uint4 *>(Vb + (size_t)tslot * ROWB + li * 16) = vraw;
+    }
 }
 
 inline hipError_t raise_lds_limit(const void *kern, size_t smem, bool &raised)
@@ -650,17 +691,23 @@ hipError_t launch_resident(const h2o_cache &c, const void *q, const void *kn, co
 }
 
 template <int DT, int D, int NW, int U>
-hipError_t launch_stream(const h2o_cache &c, const void *q, const void *kn, const void *vn,
-                         void *out, hipStream_t st)
+hipError_t launch_chunked(const h2o_cache &c, const void *q, const void *kn, const void *vn,
+                          void *out, hipStream_t st)
 {
-    const int kp = (c.k + 2) & ~1;
-    const size_t smem = (size_t)kp * 20 + (size_t)NW * D * 4 + (size_t)NW * 24 + 16;
-    auto kern = decode_stream_kernel<DT, D, NW, U>;
+    constexpr int LPR = D / Elem<DT>::EPL;
+    constexpr int RPW = 64 / LPR;
+    constexpr int OWN = U * RPW;
+    constexpr int CH = U * NW * RPW;
+    const int occ = c.t < c.k ? c.t : c.k;
+    const int chunks = (occ + CH - 1) / CH;
+    const size_t smem = (size_t)NW * OWN * (LPR + 1) * 8 + (size_t)NW * chunks * OWN * 8 +
+                        (size_t)NW * 24 + (size_t)NW * OWN * 4 + (size_t)NW * D * 4 + 16;
+    auto kern = decode_chunked_kernel<DT, D, NW, U>;
     static bool raised = false;
     hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st,
-                       H2O_DECODE_ARGS);
+                       H2O_DECODE_ARGS, chunks);
     return hipGetLastError();
 }
 
@@ -672,7 +719,7 @@ hipError_t pick(const h2o_cache &c, const void *q, const void *kn, const void *v
     // every row fits the ring (at most UMAX rounds, and at most one slot per
     // thread) the head is register-resident, with 4 waves per head for small
     // budgets so that more heads share a CU, else 8; beyond that the 8-wave
-    // kernel streams the rows through a 13-deep ring.
+    // kernel works through the head in chunks of that size.
     constexpr int LPR = D / Elem<DT>::EPL;
     constexpr int RPW = 64 / LPR;
     constexpr int UMAX = RPW * 13 <= 64 ? 13 : 8;
@@ -688,7 +735,20 @@ hipError_t pick(const h2o_cache &c, const void *q, const void *kn, const void *v
     if constexpr (UMAX > 8) {
         if (rounds <= 13) return launch_resident<DT, D, 8, 13>(c, q, kn, vn, out, st);
     }
-    return launch_stream<DT, D, 8, 13>(c, q, kn, vn, out, st);
+    // Chunked: the ring depth that wastes the fewest rounds on the last chunk
+    // (rounds past the occupied slots re-read the last row)
+    constexpr int U1 = UMAX - 2, U2 = UMAX - 4, U3 = UMAX - 6;
+    auto waste = [&](int u) { return (rounds + u - 1) / u * u - rounds; };
+    int u = UMAX;
+    if (waste(U1) < waste(u)) u = U1;
+    if (waste(U2) < waste(u)) u = U2;
+    if (U3 >= 2 && waste(U3) < waste(u)) u = U3;
+    if (u == U1) return launch_chunked<DT, D, 8, U1>(c, q, kn, vn, out, st);
+    if (u == U2) return launch_chunked<DT, D, 8, U2>(c, q, kn, vn, out, st);
+    if constexpr (U3 >= 2) {
+        if (u == U3) return launch_chunked<DT, D, 8, U3>(c, q, kn, vn, out, st);
+    }
+    return launch_chunked<DT, D, 8, UMAX>(c, q, kn, vn, out, st);
 }
 
 }  // namespace

@@ -100,13 +100,28 @@ def test_decode_dtypes_and_budgets(dt, d, n, T, heavy, recent):
 
 
 @pytest.mark.parametrize("heavy,recent,n,T", [
-    (300, 333, 700, 20),     # 633 slots: ring shorter than the stream (refills mid-stream)
-    (1500, 611, 2200, 6),    # 2111 slots: more than two bookkeeping entries per thread
+    (300, 333, 700, 20),     # 633 slots: two chunks of the register ring
+    (1500, 611, 2200, 6),    # 2111 slots: six chunks
     (2048, 2048, 4200, 3),   # the largest budget (needs the raised LDS limit)
     (1, 0, 9, 12), (0, 1, 9, 12), (1, 1, 3, 12), (4, 3, 7, 9),   # smallest budgets
 ])
 def test_decode_budget_extremes(heavy, recent, n, T):
     run_case(1, 2, 128, n, T, heavy, recent, torch.float16, 1.0, 5)
+
+
+@pytest.mark.parametrize("dt,d,heavy,recent", [("bf16", 128, 400, 433), ("f32", 128, 250, 251),
+                                               ("f32", 64, 600, 500), ("f16", 64, 700, 600),
+                                               ("bf16", 64, 0, 1100), ("f16", 128, 900, 0)])
+def test_decode_large_budget_other_types(dt, d, heavy, recent):
+    """Budgets beyond what one pass of the register ring holds (chunked kernel)
+    in the other element types and head sizes."""
+    run_case(1, 3, d, heavy + recent + 150, 10, heavy, recent, torch_dt[dt], 1.0, 17)
+
+
+def test_decode_large_budget_filling_up():
+    """Prompt shorter than a large budget: the chunked kernel first fills free
+    slots (500 -> 600 occupied), then starts evicting."""
+    run_case(1, 2, 128, 500, 130, 300, 300, torch.float16, 1.0, 19)
 
 
 @pytest.mark.parametrize("heavy,recent", [(16, 16), (0, 24), (24, 0), (7, 1)])
@@ -131,7 +146,7 @@ def test_decode_logits_far_above_the_tokens_own(dt, n, heavy, recent):
     """Steps whose cached keys score ~1000 above (and below) the token's own
     logit: exp(s_j - s_self) overflows fp64, so the kernel has to fall back to
     the true maximum as its softmax shift.  Both kernels (register-resident and
-    streaming) are covered."""
+    chunked) are covered."""
     def mutate(qs, ks, vs):
         T = qs.shape[0]
         for s in range(2, T, 3):
