@@ -84,15 +84,17 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
                     if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
                 }
                 __syncthreads();
-                if (tid == 0) {
-                    unsigned cum = 0;
-                    int b = 255;
-                    for (; b > 0; --b) {
-                        if (cum + hist[b] >= need) break;
-                        cum += hist[b];
+                // the bin in which the count from the top reaches `need`: thread r looks
+                // at bin 255 - r, the scan gives it the count of all higher bins
+                {
+                    const int bin = 255 - tid;
+                    const int cnt = tid < 256 ? (int)hist[bin] : 0;
+                    int total;
+                    const int above = block_exclusive_scan(cnt, scan_l, total);
+                    if (tid < 256 && (unsigned)above < need && (unsigned)(above + cnt) >= need) {
+                        sh_prefix = prefix | ((unsigned)bin << shift);
+                        sh_need = need - (unsigned)above;   // still needed inside that bin
                     }
-                    sh_prefix = prefix | ((unsigned)b << shift);
-                    sh_need = need - cum;              // still needed inside bin b
                 }
                 __syncthreads();
                 prefix = sh_prefix;
@@ -153,13 +155,28 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     constexpr int ROWS_PER_ROUND = SG_NT / LPR;
     const int li = tid % LPR, rsub = tid / LPR;
     const size_t pbase = (size_t)head * n * ROWB;
-    for (int s = rsub; s < k; s += ROWS_PER_ROUND) {
-        const int j = sel_l[s];
-        if (j < 0) continue;
-        const uint4 kv = *reinterpret_cast<const uint4 *>(Kp + pbase + (size_t)j * ROWB + li * 16);
-        const uint4 vv = *reinterpret_cast<const uint4 *>(Vp + pbase + (size_t)j * ROWB + li * 16);
-        *reinterpret_cast<uint4 *>(Kc + (hoff + s) * ROWB + li * 16) = kv;
-        *reinterpret_cast<uint4 *>(Vc + (hoff + s) * ROWB + li * 16) = vv;
+    // four rows per thread in flight (unconditional loads of a clamped row, so that
+    // the requests of a batch leave back to back)
+    constexpr int UNR = 4;
+    for (int s0 = rsub; s0 < k; s0 += UNR * ROWS_PER_ROUND) {
+        int j[UNR];
+        uint4 kv[UNR], vv[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int s = s0 + u * ROWS_PER_ROUND;
+            j[u] = s < k ? sel_l[s] : -1;
+            const size_t off = pbase + (size_t)max(j[u], 0) * ROWB + li * 16;
+            kv[u] = *reinterpret_cast<const uint4 *>(Kp + off);
+            vv[u] = *reinterpret_cast<const uint4 *>(Vp + off);
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int s = s0 + u * ROWS_PER_ROUND;
+            if (j[u] >= 0) {
+                *reinterpret_cast<uint4 *>(Kc + (hoff + s) * ROWB + li * 16) = kv[u];
+                *reinterpret_cast<uint4 *>(Vc + (hoff + s) * ROWB + li * 16) = vv[u];
+            }
+        }
     }
 }
 
