@@ -43,6 +43,13 @@
  *     sums are accumulated in fp64 and rounded once when stored.  With
  *     `score_f32` == 0 everything stays fp64.  All other arithmetic is fp64.
  *
+ *   - `policy` 1 (h2o_oracle_set_policy) ranks tokens by the AVERAGED score
+ *     instead of the accumulated one: accumulated score divided by the number
+ *     of queries that have scored the token (the variant App. B "Previous
+ *     Attempts" reports trying against the bias towards old tokens).  Only the
+ *     ranking changes; the stored scores stay the accumulated ones.  In
+ *     `score_f32` mode the quotient is a binary32 division.
+ *
  * Pins (tests/test_oracle_pins.py): brute-force set-function evaluation on tiny
  * inputs, reduction to textbook causal softmax attention when the budget
  * covers the sequence, harmonic-number closed form for equal logits, sliding
@@ -60,6 +67,7 @@ typedef struct h2o_oracle {
     int budget;         /* k = H + R */
     double scale;       /* logit scale */
     int score_f32;      /* store accumulated scores in binary32 */
+    int policy;         /* 0: rank by accumulated score, 1: by averaged score */
     int cap;            /* maximum number of tokens this object can see */
     int t;              /* tokens seen so far == position of the next token */
     int n_resident;
@@ -122,6 +130,30 @@ static double dot(const double *a, const double *b, int d)
     return acc;
 }
 
+/* Select what ranks a token for eviction (0 accumulated, 1 averaged score). */
+int h2o_oracle_set_policy(h2o_oracle *o, int policy)
+{
+    if (!o || (policy != 0 && policy != 1)) return -1;
+    o->policy = policy;
+    return 0;
+}
+
+/* The value that ranks position `pos` once the query at position `last_q` has
+ * been accumulated: its accumulated score, or that score divided by the
+ * number of queries that have scored it (pos .. last_q, itself included). */
+static double rank_score(const h2o_oracle *o, int pos, int last_q)
+{
+    if (o->policy == 0) return o->acc[pos];
+    const double cnt = (double)(last_q - pos + 1);
+    if (o->score_f32) {
+        volatile float a = (float)o->acc[pos];
+        volatile float c = (float)cnt;
+        volatile float r = a / c;
+        return (double)r;
+    }
+    return o->acc[pos] / cnt;
+}
+
 /* Is (score a, position pa) strictly before (score b, position pb) in the
  * eviction order: lower score first, equal scores -> lower position first. */
 static int evict_before(double a, int pa, double b, int pb)
@@ -149,7 +181,7 @@ static void compress_prompt(h2o_oracle *o, int n)
         int u = -1;
         for (int j = 0; j < first_recent; ++j) {
             if (!o->resident[j]) continue;
-            if (u < 0 || evict_before(o->acc[j], j, o->acc[u], u)) u = j;
+            if (u < 0 || evict_before(rank_score(o, j, n - 1), j, rank_score(o, u, n - 1), u)) u = j;
         }
         o->resident[u] = 0;
         o->evicted_mass += o->acc[u];
@@ -278,10 +310,11 @@ int h2o_oracle_decode(h2o_oracle *o, const double *q, const double *k_new,
         for (int j = 0; j <= last_cand; ++j) {
             if (!o->resident[j]) continue;
             ++n_cand;
-            if (evicted < 0 || evict_before(o->acc[j], j, o->acc[evicted], evicted)) {
-                second = lowest; lowest = o->acc[j]; evicted = j;
-            } else if (o->acc[j] < second) {
-                second = o->acc[j];
+            const double rj = rank_score(o, j, t);
+            if (evicted < 0 || evict_before(rj, j, lowest, evicted)) {
+                second = lowest; lowest = rj; evicted = j;
+            } else if (rj < second) {
+                second = rj;
             }
         }
         if (evicted >= 0) {

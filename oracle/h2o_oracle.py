@@ -53,6 +53,7 @@ def _load():
     lib.h2o_oracle_load_and_select.argtypes = [P, D, D, D, ctypes.c_int]
     lib.h2o_oracle_decode.argtypes = [P, D, D, D, D, I, D, D]
     lib.h2o_oracle_resync.argtypes = [P, ctypes.c_int, ctypes.c_int]
+    lib.h2o_oracle_set_policy.argtypes = [P, ctypes.c_int]
     lib.h2o_oracle_tokens_seen.argtypes = [P]
     lib.h2o_oracle_num_resident.argtypes = [P]
     lib.h2o_oracle_evicted_mass.argtypes = [P]
@@ -95,7 +96,7 @@ class OracleHead:
     """One (batch, head) pair of the H2O process, position-indexed."""
 
     def __init__(self, d: int, heavy: int, recent: int, scale: float | None = None,
-                 score_f32: bool = False, cap: int = 4096):
+                 score_f32: bool = False, cap: int = 4096, policy: int = 0):
         self._lib = _load()
         self.d, self.heavy, self.recent = int(d), int(heavy), int(recent)
         self.budget = self.heavy + self.recent
@@ -105,6 +106,8 @@ class OracleHead:
                                            1 if score_f32 else 0, self.cap)
         if not self._h:
             raise ValueError("bad oracle configuration")
+        if self._lib.h2o_oracle_set_policy(self._h, int(policy)) != 0:
+            raise ValueError("unknown eviction policy %r" % (policy,))
 
     def __del__(self):
         h = getattr(self, "_h", None)

@@ -17,7 +17,17 @@ def _store(x, dtype):
     return np.asarray(x, dtype=dtype).astype(np.float64)
 
 
-def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64):
+def _rank(acc, members, last_q, policy, score_dtype):
+    """What ranks each member after the query at position last_q: its score, or
+    (policy 1) its score divided by the number of queries that scored it."""
+    if policy == 0:
+        return {s: acc[s] for s in members}
+    if score_dtype == np.float32:
+        return {s: float(np.float32(acc[s]) / np.float32(last_q - s + 1)) for s in members}
+    return {s: acc[s] / (last_q - s + 1) for s in members}
+
+
+def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0):
     """Q, K, V: [N, d] for all N = n + T tokens.  Returns a dict with
     per-decode-step outputs, resident sets after every call, evicted tokens,
     prompt column sums and final scores."""
@@ -49,9 +59,10 @@ def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64):
         else:
             member[n - recent:n] = True
             older = list(range(n - recent))
+            r = _rank(acc, older, n - 1, policy, score_dtype)
             # best first: higher score, then higher position (so that what is
             # dropped is the lowest score and, among equals, the lowest position)
-            older.sort(key=lambda j: (acc[j], j), reverse=True)
+            older.sort(key=lambda j: (r[j], j), reverse=True)
             member[older[:heavy]] = True
         sets.append(set(np.flatnonzero(member).tolist()))
 
@@ -70,9 +81,10 @@ def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64):
         if G.sum() > k:
             members = np.flatnonzero(G).tolist()
             allowed = [v for v in members if v <= t - recent]
+            r = _rank(acc, members, t, policy, score_dtype)
             best_f = None
             for v in allowed:                     # ascending position
-                f = math.fsum(acc[s] for s in members if s != v)
+                f = math.fsum(r[s] for s in members if s != v)
                 if best_f is None or f > best_f:
                     best_f, u = f, v
             G[u] = False

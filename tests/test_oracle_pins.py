@@ -25,9 +25,9 @@ def make_inputs(seed, N, d, sigma=0.75):
     return Q, K, V
 
 
-def run_oracle(Q, K, V, n, heavy, recent, scale, score_f32=False):
+def run_oracle(Q, K, V, n, heavy, recent, scale, score_f32=False, policy=0):
     N, d = Q.shape
-    o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=N)
+    o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=N, policy=policy)
     sets, outs, evicted, lows = [], [], [], []
     colsum = attn = None
     if n > 0:
@@ -332,3 +332,90 @@ def test_worked_example_outcome():
     assert ev[:budget] == [-1] * budget                      # cache not full: expand only
     assert ev[step - 1] == victim - 1                        # 1-based token 3
     assert o.resident()[0].tolist() == [0, 1, 3]
+
+
+# ------------------------------------------------ averaged-score ranking (App. B)
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("n,T,heavy,recent", [(8, 12, 2, 2), (10, 10, 3, 1), (0, 16, 2, 3), (12, 8, 4, 0),
+                                              (14, 6, 2, 4)])
+@pytest.mark.parametrize("f32", [False, True])
+def test_average_policy_matches_brute_force(seed, n, T, heavy, recent, f32):
+    """Ranking by score / (number of queries that scored the token): the brute
+    force evaluates F(G \\ {v}) = sum of the averaged scores for every allowed v."""
+    d = 4
+    Q, K, V = make_inputs(5000 + seed, n + T, d)
+    scale = 0.5
+    o, got = run_oracle(Q, K, V, n, heavy, recent, scale, score_f32=f32, policy=1)
+    ref = brute_h2o(Q, K, V, n, heavy, recent, scale, np.float32 if f32 else np.float64, policy=1)
+    for lo, se in got["lows"]:
+        if np.isfinite(se):
+            assert se - lo > 1e-9
+    assert got["sets"] == ref["sets"]
+    assert got["evicted"] == ref["evicted"]
+    np.testing.assert_allclose(got["outs"], ref["outs"], rtol=1e-12, atol=1e-13)
+    pos, sc = o.resident()
+    # what is stored stays the ACCUMULATED score
+    if f32:
+        assert np.array_equal(sc, ref["acc"][pos])
+    else:
+        np.testing.assert_allclose(sc, ref["acc"][pos], rtol=1e-12, atol=1e-14)
+
+
+def test_average_policy_differs_from_accumulated_where_it_should():
+    """An old token with a long record of small scores against a younger one
+    with a short record of larger scores: the accumulated score keeps the old
+    one, the averaged score keeps the young one.  Scores are constructed through
+    load_and_select (positions 0 and 6 of an 8-token prompt, window of one)."""
+    d, n = 2, 8
+    K = np.zeros((n, d)); V = np.zeros((n, d))
+    score = np.full(n, 5.0)                # everything else is clearly better
+    score[0] = 1.6                         # 8 queries: average 0.2
+    score[6] = 1.0                         # 2 queries: average 0.5
+    kept = {}
+    for policy in (0, 1):
+        o = OracleHead(d, n - 2, 1, 1.0, cap=n, policy=policy)   # drop exactly one older token
+        o.load_and_select(K, V, score)
+        kept[policy] = set(o.resident()[0].tolist())
+    assert 6 not in kept[0] and 0 in kept[0]
+    assert 0 not in kept[1] and 6 in kept[1]
+
+
+def test_average_policy_uniform_attention_closed_form():
+    """Equal logits, prompt 12, budget 3 + 2.  Every query spreads 1/|G| over its
+    |G| tokens, so scores are sums of unit fractions:
+      * step t = 12 evicts token 10 (just out of the window): scored by the
+        queries 10, 11 (prompt rows: 1/11, 1/12) and 12 (cache of 6: 1/6),
+        average (1/11 + 1/12 + 1/6) / 3;
+      * a token that arrives once the cache is full averages exactly 1/6, while
+        an old heavy hitter's average keeps falling towards 1/6 from the prompt
+        rows it collected: token 2 has (H_12 - H_2 + 3/6) / 13 < 1/6 at t = 14
+        and is evicted there -- under the accumulated score it never is."""
+    d, n, T, heavy, recent = 3, 12, 10, 3, 2
+    Q = np.zeros((n + T, d)); K = np.ones((n + T, d)); V = np.arange((n + T) * d, dtype=float).reshape(-1, d)
+    H = lambda m: sum(1.0 / i for i in range(1, m + 1))
+    avg = OracleHead(d, heavy, recent, 1.0, cap=n + T, policy=1)
+    acc = OracleHead(d, heavy, recent, 1.0, cap=n + T, policy=0)
+    for o in (avg, acc):
+        o.prefill(Q[:n], K[:n], V[:n])
+        assert set(o.resident()[0].tolist()) == set(range(heavy)) | set(range(n - recent, n))
+    evicted = {}
+    for t in range(n, n + T):
+        ra = avg.decode(Q[t], K[t], V[t])
+        rs = acc.decode(Q[t], K[t], V[t])
+        evicted[t] = ra.evicted
+        assert rs.evicted == t - recent               # accumulated score: always the newcomer
+        if t == 12:
+            assert ra.evicted == 10
+            assert ra.lowest == pytest.approx((1 / 11 + 1 / 12 + 1 / 6) / 3, rel=1e-13)
+        if t == 14:
+            assert ra.evicted == 2
+            assert ra.lowest == pytest.approx((H(12) - H(2) + 3 / 6) / 13, rel=1e-13)
+            assert ra.lowest < 1 / 6
+    assert evicted[13] == 11
+    assert set(range(heavy)) <= set(acc.resident()[0].tolist())
+    assert 2 not in set(avg.resident()[0].tolist())
+
+
+def test_policy_argument_is_validated():
+    with pytest.raises(ValueError):
+        OracleHead(4, 2, 2, 1.0, cap=8, policy=2)
