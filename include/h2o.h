@@ -59,6 +59,14 @@ typedef enum h2o_status {
 
 typedef enum h2o_dtype { H2O_F32 = 0, H2O_F16 = 1, H2O_BF16 = 2 } h2o_dtype;
 
+/* What ranks a cached token when one has to be evicted (and when the prompt is
+ * compressed).  H2O_RANK_ACCUMULATED is the method (Algorithm 2: the accumulated
+ * attention score).  H2O_RANK_AVERAGED divides that score by the number of
+ * queries that have scored the token (its own included), the variant the paper
+ * reports trying against the bias towards old tokens (App. B, "Previous
+ * Attempts"); only the ranking changes, the stored scores stay accumulated. */
+typedef enum h2o_rank { H2O_RANK_ACCUMULATED = 0, H2O_RANK_AVERAGED = 1 } h2o_rank;
+
 /* Largest supported budget (heavy + recent) and prompt length. */
 #define H2O_MAX_BUDGET 4096
 #define H2O_MAX_PROMPT 65536
@@ -71,6 +79,7 @@ typedef struct h2o_config {
     int32_t recent;     /* R >= 0, recent-window share; H + R >= 1 */
     int32_t dtype;      /* h2o_dtype of Q/K/V/q/k/v/out and of the cached K/V */
     float scale;        /* logit scale; 0 selects 1/sqrt(head_dim) */
+    int32_t rank;       /* h2o_rank; 0 = the method's accumulated score */
 } h2o_config;
 
 typedef struct h2o_cache h2o_cache;   /* opaque host-side handle */
@@ -118,7 +127,8 @@ int h2o_prefill_colsum(const h2o_config *cfg, const void *Q, const void *K,
  * Prompt compression (App. A: "K heavy hitters and K recent tokens ...
  * otherwise return all"): given a score per prompt token, keep the last
  * `recent` tokens and the `heavy` highest-scoring older ones (all n tokens if
- * n <= heavy + recent; equal scores: the higher position is kept), copy their
+ * n <= heavy + recent; equal scores: the higher position is kept; with
+ * H2O_RANK_AVERAGED the older tokens are ranked by score[j] / (n - j)), copy their
  * K/V rows into slots in ascending position order, set acc/pos, mark the rest
  * free, and set t = n.  The cache must be empty (fresh or reset).
  *   K, V    [batch, heads, n, head_dim];   score  float [batch, heads, n]
@@ -186,8 +196,9 @@ int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K,
  *   3. out = sum_j p_j V[slot j] + p_self * v_new;
  *   4. acc[j] += p_j (binary32 add of the binary32-rounded probability);
  *   5. if a slot is free the new token takes the lowest-indexed free slot;
- *      otherwise the occupied slot with the smallest (acc, pos) among those
- *      with pos <= t - recent is evicted (with recent == 0 the new token,
+ *      otherwise the occupied slot with the smallest (rank value, pos) among
+ *      those with pos <= t - recent is evicted, the rank value being acc or,
+ *      for H2O_RANK_AVERAGED, the binary32 quotient acc / (t - pos + 1) (with recent == 0 the new token,
  *      scored p_self, competes and may itself be dropped);
  *   6. the chosen slot gets K = k_new, V = v_new, acc = p_self, pos = t.
  * Then t becomes t + 1.  The cache is read exactly once.

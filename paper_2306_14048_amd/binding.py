@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libh2o_hip.so")
 
 H2O_OK, H2O_EINVAL, H2O_EUNSUPPORTED, H2O_ENOMEM, H2O_ESTATE, H2O_EHIP = 0, -1, -2, -3, -4, -5
 H2O_F32, H2O_F16, H2O_BF16 = 0, 1, 2
+H2O_RANK_ACCUMULATED, H2O_RANK_AVERAGED = 0, 1
 H2O_MAX_BUDGET = 4096
 H2O_MAX_PROMPT = 65536
 
@@ -35,7 +36,7 @@ EXPORTS = (
 class h2o_config(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("heavy", ctypes.c_int32), ("recent", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("scale", ctypes.c_float)]
+                ("scale", ctypes.c_float), ("rank", ctypes.c_int32)]
 
 
 class H2OError(RuntimeError):
@@ -97,11 +98,11 @@ def _check(rc: int, where: str) -> None:
         raise H2OError(rc, where)
 
 
-def make_config(batch, heads, head_dim, heavy, recent, dtype, scale=0.0) -> h2o_config:
+def make_config(batch, heads, head_dim, heavy, recent, dtype, scale=0.0, rank=0) -> h2o_config:
     if isinstance(dtype, torch.dtype):
         dtype = DTYPES[dtype]
     return h2o_config(int(batch), int(heads), int(head_dim), int(heavy), int(recent), int(dtype),
-                      float(scale))
+                      float(scale), int(rank))
 
 
 def h2o_status_str(status: int) -> str:
@@ -199,8 +200,8 @@ class H2OCache:
     one cache; methods forward to the entry points of the same name."""
 
     def __init__(self, batch, heads, head_dim, heavy, recent, dtype=torch.float16, scale=0.0,
-                 device="cuda", stream=None):
-        self.cfg = make_config(batch, heads, head_dim, heavy, recent, dtype, scale)
+                 device="cuda", stream=None, rank=0):
+        self.cfg = make_config(batch, heads, head_dim, heavy, recent, dtype, scale, rank)
         self.dtype = dtype if isinstance(dtype, torch.dtype) else TORCH_DTYPES[dtype]
         self.device = torch.device(device)
         self.budget = int(heavy) + int(recent)

@@ -152,6 +152,15 @@ __device__ inline double wave_sum(double v)
 }
 constexpr unsigned long long NO_CANDIDATE = ~0ull;
 
+// What ranks a slot for eviction after the query at position t: its accumulated
+// score, or (averaged ranking) that score over the number of queries that have
+// scored the token, t - pos + 1, as a correctly rounded binary32 quotient.  The
+// new token itself has been scored once, so its value is its first score either way.
+__device__ inline float rank_value(float acc, int pos, int t, int rank)
+{
+    return rank == H2O_RANK_AVERAGED ? __fdiv_rn(acc, (float)(t - pos + 1)) : acc;
+}
+
 // ---- pieces shared by the two kernels -------------------------------------------
 
 // Adds this lane's fp32 partial output (EPL columns of row group `sub`) into the
@@ -195,7 +204,7 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
-    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale)
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank)
 {
     using E = Elem<DT>;
     using T = typename E::T;
@@ -354,7 +363,8 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     // which fmin drops: the key reduction is a plain fp64 minimum.
     unsigned long long key = NO_CANDIDATE;
     if (owner && pos_j <= t - recent)                        // window after this step = {t-R+1..t}
-        key = ((unsigned long long)__float_as_uint(acc_j) << 32) | (unsigned)pos_j;
+        key = ((unsigned long long)__float_as_uint(rank_value(acc_j, pos_j, t, rank)) << 32) |
+              (unsigned)pos_j;
     {
         const double kw = wave_min_f64(__longlong_as_double((long long)key));
         if (lane == 0) red_key[wave] = kw;
@@ -421,7 +431,7 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
-    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int chunks)
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank, int chunks)
 {
     using E = Elem<DT>;
     using T = typename E::T;
@@ -592,7 +602,8 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
             acc_g[hoff + slot] = acc_j;
             if (pos_j <= t - recent) {                           // window after this step = {t-R+1..t}
                 const unsigned long long key =
-                    ((unsigned long long)__float_as_uint(acc_j) << 32) | (unsigned)pos_j;
+                    ((unsigned long long)__float_as_uint(rank_value(acc_j, pos_j, t, rank)) << 32) |
+                    (unsigned)pos_j;
                 if (key < best) { best = key; best_slot = slot; }
             }
         }
@@ -671,7 +682,7 @@ inline hipError_t raise_lds_limit(const void *kern, size_t smem, bool &raised)
 #define H2O_DECODE_ARGS                                                                         \
     c.K, c.V, c.acc, c.pos, static_cast<const char *>(q), static_cast<const char *>(kn),        \
         static_cast<const char *>(vn), static_cast<char *>(out), c.k, (c.t < c.k ? c.t : c.k),  \
-        c.t, c.cfg.recent, c.scale
+        c.t, c.cfg.recent, c.scale, c.cfg.rank
 
 template <int DT, int D, int NW, int U>
 hipError_t launch_resident(const h2o_cache &c, const void *q, const void *kn, const void *vn,

@@ -16,6 +16,7 @@ int check_config(const h2o_config *c)
     if ((int64_t)c->heavy + c->recent < 1) return H2O_EINVAL;
     if (c->dtype != H2O_F32 && c->dtype != H2O_F16 && c->dtype != H2O_BF16) return H2O_EINVAL;
     if (!(c->scale >= 0.0f) || !(c->scale < 3.0e38f)) return H2O_EINVAL;
+    if (c->rank != H2O_RANK_ACCUMULATED && c->rank != H2O_RANK_AVERAGED) return H2O_EINVAL;
     if (c->head_dim != 64 && c->head_dim != 128) return H2O_EUNSUPPORTED;
     if ((int64_t)c->heavy + c->recent > H2O_MAX_BUDGET) return H2O_EUNSUPPORTED;
     if ((int64_t)c->batch * c->heads > (1 << 24)) return H2O_EUNSUPPORTED;

@@ -52,7 +52,7 @@ template <int ROWB>
 __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     const char *__restrict__ Kp, const char *__restrict__ Vp, const float *__restrict__ score,
     int n, char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
-    int32_t *__restrict__ pos_g, int k, int heavy, int recent)
+    int32_t *__restrict__ pos_g, int k, int heavy, int recent, int rank)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     int *sel_l = reinterpret_cast<int *>(smem);        // [k] slot -> prompt position
@@ -63,6 +63,12 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     const int head = blockIdx.x, tid = threadIdx.x;
     const float *sc = score + (size_t)head * n;
     const size_t hoff = (size_t)head * k;
+
+    // what ranks an older token: its score, or (averaged ranking) its score over
+    // the n - j prompt queries that scored it
+    auto ranked = [&](float v, int j) {
+        return rank == H2O_RANK_AVERAGED ? __fdiv_rn(v, (float)(n - j)) : v;
+    };
 
     for (int s = tid; s < k; s += SG_NT) sel_l[s] = -1;
 
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
                 for (int b = tid; b < 256; b += SG_NT) hist[b] = 0;
                 __syncthreads();
                 for (int j = tid; j < older; j += SG_NT) {
-                    const unsigned key = order_key(sc[j]);
+                    const unsigned key = order_key(ranked(sc[j], j));
                     if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
                 }
                 __syncthreads();
@@ -109,7 +115,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
         const int j0 = min(n, tid * per), j1 = min(n, j0 + per);
         int eq_cnt = 0;
         if (heavy > 0)
-            for (int j = j0; j < min(j1, older); ++j) eq_cnt += order_key(sc[j]) == thr;
+            for (int j = j0; j < min(j1, older); ++j) eq_cnt += order_key(ranked(sc[j], j)) == thr;
         int eq_total;
         int eq_before = block_exclusive_scan(eq_cnt, scan_l, eq_total);
         // among equal scores the higher positions are kept: the last `need` of them
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
             for (int j = j0; j < j1; ++j) {
                 bool keep = j >= older;
                 if (!keep && heavy > 0) {
-                    const unsigned key = order_key(sc[j]);
+                    const unsigned key = order_key(ranked(sc[j], j));
                     if (key > thr) keep = true;
                     else if (key == thr) { keep = e >= eq_first_kept; ++e; }
                 }
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
             for (int j = j0; j < j1; ++j) {
                 bool keep = j >= older;
                 if (!keep && heavy > 0) {
-                    const unsigned key = order_key(sc[j]);
+                    const unsigned key = order_key(ranked(sc[j], j));
                     if (key > thr) keep = true;
                     else if (key == thr) { keep = e >= eq_first_kept; ++e; }
                 }
@@ -205,7 +211,7 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
     const char *Kp = static_cast<const char *>(K), *Vp = static_cast<const char *>(V);
 #define H2O_SG(RB)                                                                              \
     hipLaunchKernelGGL((select_gather_kernel<RB>), dim3(heads), dim3(SG_NT), smem, st, Kp, Vp,   \
-                       score, n, c.K, c.V, c.acc, c.pos, c.k, c.cfg.heavy, c.cfg.recent)
+                       score, n, c.K, c.V, c.acc, c.pos, c.k, c.cfg.heavy, c.cfg.recent, c.cfg.rank)
     switch (rowb) {
     case 128: H2O_SG(128); break;
     case 256: H2O_SG(256); break;

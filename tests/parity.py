@@ -60,7 +60,8 @@ class DecodeStats:
         self.max_score_rel = max(self.max_score_rel, o.max_score_rel)
 
 
-def oracle_prefill_heads(Q, K, V, heads, heavy, recent, scale, cap, score_f32=True, threads=None):
+def oracle_prefill_heads(Q, K, V, heads, heavy, recent, scale, cap, score_f32=True, threads=None,
+                         policy=0):
     """Runs the oracle's prompt phase for the listed (b, h) pairs.
     Q, K, V: torch tensors [B, Hh, n, d] (any device).  Returns
     ({(b, h): OracleHead}, {(b, h): colsum float64[n]})."""
@@ -68,7 +69,7 @@ def oracle_prefill_heads(Q, K, V, heads, heavy, recent, scale, cap, score_f32=Tr
 
     def one(bh):
         b, h = bh
-        o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=cap)
+        o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=cap, policy=policy)
         col, _ = o.prefill(host64(Q[b, h]), host64(K[b, h]), host64(V[b, h]))
         return o, col
 
@@ -135,7 +136,15 @@ def run_gpu_decode(cache, qs, ks, vs, snapshot_heads=None):
     return outs.cpu(), snaps.cpu()
 
 
-def check_head_decode(o: OracleHead, qs, ks, vs, outs, snaps, recent, out_tol) -> DecodeStats:
+def rank_of(o: OracleHead, pos: int, t: int, policy: int) -> float:
+    """The value that ranks `pos` after the query at position t, in the precision
+    the scores are stored in (binary32): the score itself or, for the averaged
+    ranking, score / (t - pos + 1)."""
+    s = np.float32(o.score(pos))
+    return float(s) if policy == 0 else float(s / np.float32(t - pos + 1))
+
+
+def check_head_decode(o: OracleHead, qs, ks, vs, outs, snaps, recent, out_tol, policy=0) -> DecodeStats:
     """Steps one oracle head through T steps and compares with the device's
     per-step outputs [T, d] and slot tables [T, k] of the same head."""
     out_tol = out_tol + OUT_STORE_SLACK[outs.dtype]
@@ -172,7 +181,7 @@ def check_head_decode(o: OracleHead, qs, ks, vs, outs, snaps, recent, out_tol) -
             ok = (len(only_ref) == 1 and len(only_gpu) == 1 and r.evicted in only_gpu)
             if ok:
                 g = next(iter(only_ref))
-                sg = o.score(g)
+                sg = rank_of(o, g, t, policy)
                 ok = (g <= t - recent and
                       (sg - r.lowest) <= NEAR_TIE * max(abs(sg), abs(r.lowest)))
             assert ok, ("kept-set mismatch at step %d (t=%d): device-only %s oracle-only %s, "

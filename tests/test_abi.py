@@ -44,8 +44,12 @@ def test_size_queries_and_validation(hb):
     bad = [hb.make_config(0, 32, 128, 4, 4, hb.H2O_F16), hb.make_config(1, 1, 96, 4, 4, hb.H2O_F16),
            hb.make_config(1, 1, 128, 0, 0, hb.H2O_F16), hb.make_config(1, 1, 128, -1, 4, hb.H2O_F16),
            hb.make_config(1, 1, 128, 4000, 4000, hb.H2O_F16), hb.make_config(1, 1, 128, 4, 4, 7)]
+    bad.append(hb.make_config(1, 1, 128, 4, 4, hb.H2O_F16, rank=2))
     for c in bad:
         assert hb.h2o_cache_bytes(c) == 0
+    assert hb.h2o_cache_bytes(hb.make_config(16, 32, 128, 205, 205, hb.H2O_F16, rank=hb.H2O_RANK_AVERAGED)) \
+        == 2 * kv + 2 * meta
+    assert ctypes.sizeof(hb.h2o_config) == 32
     assert hb.h2o_prefill_workspace_bytes(ok, 0) == 0
     assert hb.h2o_prefill_workspace_bytes(ok, hb.H2O_MAX_PROMPT + 1) == 0
     # transposed V padded to whole 64-key tiles, then the scoring scratch

@@ -19,7 +19,7 @@ torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 
 def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sample=None,
-             permute_slots=False, mutate=None):
+             permute_slots=False, mutate=None, rank=0):
     from paper_2306_14048_amd import binding as hb, synth
     dev = torch.device("cuda:0")
     k = heavy + recent
@@ -31,13 +31,13 @@ def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sampl
     qs, ks, vs = synth.make_steps(B, Hh, d, T, dtype, sigma, dev, seed)
     if mutate is not None:
         mutate(qs, ks, vs)                # edits the shared inputs before either side sees them
-    cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, scale, device=dev)
+    cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, scale, device=dev, rank=rank)
     all_heads = [(b, h) for b in range(B) for h in range(Hh)]
     if n > 0:
         Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, sigma, dev, seed)
         Qh, Kh, Vh = Q.cpu(), K.cpu(), V.cpu()
         oracles, _ = parity.oracle_prefill_heads(Qh, Kh, Vh, all_heads, heavy, recent, scale_d,
-                                                 cap=n + T)
+                                                 cap=n + T, policy=rank)
         Kc, Vc, acc, pos = parity.cache_state_from_oracles(oracles, B, Hh, k, Kh, Vh)
         if permute_slots:
             # occupied slots stay a prefix, their order inside it is shuffled per head
@@ -49,7 +49,8 @@ def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sampl
                 acc[b, h, :c] = acc[b, h, perm]; pos[b, h, :c] = pos[b, h, perm]
         cache.restore(Kc.to(dev), Vc.to(dev), acc.to(dev), pos.to(dev), n)
     else:
-        oracles = {bh: OracleHead(d, heavy, recent, scale_d, score_f32=True, cap=T) for bh in all_heads}
+        oracles = {bh: OracleHead(d, heavy, recent, scale_d, score_f32=True, cap=T, policy=rank)
+                   for bh in all_heads}
     outs, snaps = parity.run_gpu_decode(cache, qs, ks, vs)
     pos_f, acc_f = cache.snapshot()
     torch.cuda.synchronize()
@@ -61,7 +62,7 @@ def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sampl
     def one(bh):
         b, h = bh
         st = parity.check_head_decode(oracles[bh], qh[:, b, h], kh[:, b, h], vh[:, b, h],
-                                      outs[:, b, h], snaps[:, b, h], recent, tol)
+                                      outs[:, b, h], snaps[:, b, h], recent, tol, policy=rank)
         parity.check_final_scores(oracles[bh], pos_f[b, h], acc_f[b, h], st)
         return st
 
@@ -122,6 +123,15 @@ def test_decode_large_budget_filling_up():
     """Prompt shorter than a large budget: the chunked kernel first fills free
     slots (500 -> 600 occupied), then starts evicting."""
     run_case(1, 2, 128, 500, 130, 300, 300, torch.float16, 1.0, 19)
+
+
+@pytest.mark.parametrize("dt,d,n,T,heavy,recent", [
+    ("f16", 128, 300, 60, 50, 50), ("bf16", 64, 0, 90, 20, 12), ("f32", 64, 200, 40, 24, 0),
+    ("f16", 128, 700, 30, 300, 300), ("bf16", 128, 96, 50, 13, 10)])
+def test_decode_averaged_ranking(dt, d, n, T, heavy, recent):
+    """Eviction by accumulated score / number of queries that scored the token
+    (both kernels, also from an empty cache and with recent = 0)."""
+    run_case(2, 3, d, n, T, heavy, recent, torch_dt[dt], 1.0, 23, rank=1)
 
 
 @pytest.mark.parametrize("heavy,recent", [(16, 16), (0, 24), (24, 0), (7, 1)])

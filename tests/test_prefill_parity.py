@@ -72,7 +72,7 @@ def test_colsum_explicit_scale_heavy_tail():
     colsum_case(1, 2, 64, 260, torch.bfloat16, 1.25, 3, scale=0.3)
 
 
-def select_case(B, Hh, d, n, heavy, recent, dtype, score, seed):
+def select_case(B, Hh, d, n, heavy, recent, dtype, score, seed, rank=0):
     """Device select+gather on given scores against the oracle's compression of
     the same scores: same kept positions in ascending slot order, identical
     rows, identical scores."""
@@ -80,7 +80,7 @@ def select_case(B, Hh, d, n, heavy, recent, dtype, score, seed):
     dev = torch.device("cuda:0")
     k = heavy + recent
     _, K, V = synth.make_prompt(B, Hh, n, d, dtype, 1.0, dev, seed)
-    cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, device=dev)
+    cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, device=dev, rank=rank)
     sc = torch.from_numpy(score.astype(np.float32)).to(dev)
     cache.prefill_select(K, V, sc)
     pos, acc = cache.snapshot()
@@ -91,7 +91,7 @@ def select_case(B, Hh, d, n, heavy, recent, dtype, score, seed):
     Kh, Vh = K.cpu(), V.cpu()
     for b in range(B):
         for h in range(Hh):
-            o = OracleHead(d, heavy, recent, 1.0, score_f32=True, cap=n)
+            o = OracleHead(d, heavy, recent, 1.0, score_f32=True, cap=n, policy=rank)
             o.load_and_select(parity.host64(Kh[b, h]), parity.host64(Vh[b, h]),
                               score[b, h].astype(np.float32).astype(np.float64))
             rp, rs = o.resident()
@@ -121,6 +121,20 @@ def test_select_gather_exact(n, heavy, recent, kind):
         score[..., ::7] = 0.0
         score[..., 3::11] = -0.0
     select_case(B, Hh, 128, n, heavy, recent, torch.float16, score, 5)
+
+
+@pytest.mark.parametrize("n,heavy,recent", [(50, 6, 9), (1000, 103, 102), (4096, 410, 409), (200, 16, 0)])
+@pytest.mark.parametrize("kind", ["random", "ties"])
+def test_select_gather_averaged_ranking(n, heavy, recent, kind):
+    """Prompt compression with the older tokens ranked by score / (n - position)."""
+    rng = np.random.default_rng(n * 13 + len(kind))
+    B, Hh = 2, 2
+    if kind == "random":
+        score = rng.random((B, Hh, n)) * 5
+    else:
+        # equal AVERAGES on purpose: score proportional to the number of queries
+        score = np.round(rng.random((B, Hh, n)) * 3 + 1) * (n - np.arange(n)) / 8.0
+    select_case(B, Hh, 128, n, heavy, recent, torch.float16, score, 5, rank=1)
 
 
 def test_select_gather_other_row_sizes():
