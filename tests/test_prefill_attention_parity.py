@@ -189,3 +189,60 @@ def test_attention_rejects_f32():
     with pytest.raises(hb.H2OError) as ei:
         hb.h2o_prefill_attention(cfg, x, x, x, 64, ws, ws.numel(), x, None)
     assert ei.value.status == hb.H2O_EUNSUPPORTED
+
+
+def test_largest_prompt_sampled():
+    """The largest supported prompt (65536 tokens), one head, in the launch shape
+    any caller gets: attention rows and row log-sum-exps of sampled queries, and
+    the column sums of the last columns (each needs only its own rows), against a
+    float64 evaluation of the definitions on the same tensors; plus what holds at
+    any size: the column sums are positive and add up to n.  (The oracle's prompt
+    phase is quadratic and would take hours here.)"""
+    from paper_2306_14048_amd import binding as hb, synth
+    dev = torch.device("cuda:0")
+    B, Hh, d, n, dtype = 1, 1, 64, hb.H2O_MAX_PROMPT, torch.float16
+    Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, 1.0, dev, 41)
+    cache = hb.H2OCache(B, Hh, d, 2048, 2048, dtype, device=dev)
+    need = hb.h2o_prefill_attention_workspace_bytes(cache.cfg, n)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = torch.empty_like(Q)
+    col = torch.empty((B, Hh, n), dtype=torch.float32, device=dev)
+    hb.h2o_prefill_attention_scores(cache.handle, Q, K, V, n, ws, need, out, col)
+    lse = torch.empty((B, Hh, n), dtype=torch.float32, device=dev)
+    hb.h2o_prefill_attention(cache.cfg, Q, K, V, n, ws, need, out, lse)
+    col2 = hb.prefill_colsum(cache.cfg, Q, K)                 # the two-pass scoring path
+    torch.cuda.synchronize()
+    Qd, Kd, Vd = (x[0, 0].cpu().double().numpy() for x in (Q, K, V))
+    got, lse, col, col2 = (x[0, 0].cpu().double().numpy() for x in (out, lse, col, col2))
+    scale = parity.oracle_scale(d)
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 255, 256, n - 1], rng.integers(0, n, 40)]))
+    ref_lse_all = {}
+    for i in rows:
+        s = scale * (Kd[: i + 1] @ Qd[i])
+        m = s.max()
+        e = np.exp(s - m)
+        ref_lse_all[int(i)] = m + np.log(e.sum())
+        ref = (e / e.sum()) @ Vd[: i + 1]
+        check_rows(got[i][None], ref[None], dtype, "row %d" % i)
+        assert abs(lse[i] - ref_lse_all[int(i)]) <= 2e-5 * max(1.0, abs(ref_lse_all[int(i)]))
+    # last columns: c_j = sum_{i >= j} exp(s_ij - LSE_i) with every LSE_i from float64
+    tail = 48
+    S = scale * (Qd[n - tail:] @ Kd.T)                        # rows n-tail .. n-1, all keys
+    for r in range(tail):
+        S[r, n - tail + r + 1:] = -np.inf
+    m = S.max(-1, keepdims=True)
+    L = m[:, 0] + np.log(np.exp(S - m).sum(-1))
+    P = np.exp(S - L[:, None])
+    ref_tail = np.array([P[j - (n - tail):, j].sum() for j in range(n - tail, n)])
+    for c in (col, col2):
+        assert np.all(np.abs(c[n - tail:] - ref_tail) <= COLSUM_RTOL * ref_tail + COLSUM_ATOL)
+        assert np.all(c > 0) and np.all(np.isfinite(c))
+        assert abs(c.sum() - n) <= 1e-4 * n
+    # the two scoring paths agree column by column
+    assert np.all(np.abs(col - col2) <= 2 * COLSUM_RTOL * np.abs(col2) + COLSUM_ATOL)
+    # compression: budget 4096 of 65536, window resident, positions ascending
+    pos, _ = cache.snapshot()
+    pos = pos[0, 0].cpu().numpy()
+    assert np.all(np.diff(pos) > 0) and pos[-2048:].tolist() == list(range(n - 2048, n))
+    cache.close()
