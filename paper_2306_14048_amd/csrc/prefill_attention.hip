@@ -163,7 +163,10 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
 
     extern __shared__ __align__(16) unsigned char smem[];   // [ANS][STAGE]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // (the wave index as a scalar: branches on it are then uniform for the compiler
+    // too, which otherwise keeps a second copy of the accumulators around them)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int grp = wave >> 2;
     const int nblk = (n + SROWS - 1) / SROWS;

@@ -147,7 +147,9 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     unsigned char *tile_l = smem;                                        // [NTB][TILEB]
     float *lse_l = reinterpret_cast<float *>(smem + NTB * TILEB);        // [NLB][BN] (pass 2)
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // (the wave index as a scalar: branches on it are then uniform for the compiler too)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int grp = wave >> 2;            // ping-pong group
     const int nblk = (n + SROWS - 1) / SROWS;
