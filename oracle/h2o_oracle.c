@@ -50,6 +50,16 @@
  *     ranking changes; the stored scores stay the accumulated ones.  In
  *     `score_f32` mode the quotient is a binary32 division.
  *
+ *   - chunked prompt processing (h2o_oracle_prefill_chunk): the paper gives the
+ *     two ends, token-by-token eviction over the whole sequence (Algorithm 1)
+ *     and one-shot compression after full attention over the prompt (App. A).
+ *     A chunk of m tokens is the step in between: every token of the chunk
+ *     attends to the tokens in the cache and, causally, to the chunk's own
+ *     tokens (nothing is evicted inside a chunk); the chunk's probabilities
+ *     are added to the scores (Algorithm 2's accumulate line); then cache plus
+ *     chunk is compressed by the prompt rule.  m = 1 is the generation step,
+ *     one chunk holding the whole prompt is the one-shot prompt phase.
+ *
  * Pins (tests/test_oracle_pins.py): brute-force set-function evaluation on tiny
  * inputs, reduction to textbook causal softmax attention when the budget
  * covers the sequence, harmonic-number closed form for equal logits, sliding
@@ -235,6 +245,87 @@ int h2o_oracle_prefill(h2o_oracle *o, const double *Q, const double *K,
         for (int j = 0; j < n; ++j) o->acc[j] = (double)(float)o->acc[j];
 
     compress_prompt(o, n);
+    return 0;
+}
+
+/*
+ * The next m prompt tokens as one chunk (positions t .. t+m-1).  Q, K, V are
+ * [m][d].  Token t+i attends to the resident tokens and to the chunk's tokens
+ * t .. t+i; the column sums of these m softmax rows are added to the stored
+ * scores (in binary32 storage: each column's chunk sum is rounded to binary32
+ * and added in binary32); all chunk tokens become resident; if more than
+ * `budget` tokens are resident the `recent` last positions stay and, among the
+ * older resident ones, the smallest (rank value, position) is evicted
+ * repeatedly until `heavy` of them remain.
+ *   colsum_out (nullable, [t+m]): the chunk's column sums in fp64 by POSITION
+ *       (zero for positions that were not attended to)
+ *   attn_out   (nullable, [m][d]): attention output of every chunk token
+ * Returns 0, or -1 on bad arguments / capacity.
+ */
+int h2o_oracle_prefill_chunk(h2o_oracle *o, const double *Q, const double *K,
+                             const double *V, int m, double *colsum_out,
+                             double *attn_out)
+{
+    if (!o || !Q || !K || !V || m <= 0 || o->t + m > o->cap) return -1;
+    const int d = o->d, t0 = o->t, t1 = o->t + m;
+    memcpy(o->K + (size_t)t0 * d, K, (size_t)m * d * sizeof(double));
+    memcpy(o->V + (size_t)t0 * d, V, (size_t)m * d * sizeof(double));
+    double *chunk = (double *)calloc((size_t)t1, sizeof(double));
+    if (!chunk) return -1;
+    for (int j = t0; j < t1; ++j) { o->acc[j] = 0.0; o->resident[j] = 0; }
+
+    for (int i = 0; i < m; ++i) {
+        const int pi = t0 + i;                    /* position of this query */
+        const double *qi = Q + (size_t)i * d;
+        /* visible: resident tokens (all older than the chunk) and chunk tokens <= pi */
+        double mx = -INFINITY;
+        for (int j = 0; j <= pi; ++j) {
+            if (j < t0 && !o->resident[j]) continue;
+            o->s[j] = o->scale * dot(qi, o->K + (size_t)j * d, d);
+            if (o->s[j] > mx) mx = o->s[j];
+        }
+        double D = 0.0;
+        for (int j = 0; j <= pi; ++j) {
+            if (j < t0 && !o->resident[j]) continue;
+            o->p[j] = exp(o->s[j] - mx); D += o->p[j];
+        }
+        if (attn_out) for (int c = 0; c < d; ++c) attn_out[(size_t)i * d + c] = 0.0;
+        for (int j = 0; j <= pi; ++j) {
+            if (j < t0 && !o->resident[j]) continue;
+            o->p[j] /= D;
+            chunk[j] += o->p[j];
+            if (attn_out) {
+                const double *vj = o->V + (size_t)j * d;
+                for (int c = 0; c < d; ++c) attn_out[(size_t)i * d + c] += o->p[j] * vj[c];
+            }
+        }
+    }
+    o->queries += (double)m;
+    if (colsum_out) memcpy(colsum_out, chunk, (size_t)t1 * sizeof(double));
+    for (int j = 0; j < t1; ++j) {
+        if (j < t0 && !o->resident[j]) continue;
+        o->acc[j] = add_score(o, o->acc[j], chunk[j]);
+    }
+    free(chunk);
+    for (int j = t0; j < t1; ++j) o->resident[j] = 1;
+    o->n_resident += m;
+    o->t = t1;
+
+    if (o->n_resident > o->budget) {
+        const int first_recent = t1 - o->recent;  /* window = [t1-R, t1) */
+        int older = 0;
+        for (int j = 0; j < first_recent; ++j) older += o->resident[j];
+        while (older > o->heavy) {
+            int u = -1;
+            for (int j = 0; j < first_recent; ++j) {
+                if (!o->resident[j]) continue;
+                if (u < 0 || evict_before(rank_score(o, j, t1 - 1), j, rank_score(o, u, t1 - 1), u)) u = j;
+            }
+            o->resident[u] = 0;
+            o->evicted_mass += o->acc[u];
+            --older; --o->n_resident;
+        }
+    }
     return 0;
 }
 

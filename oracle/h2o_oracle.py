@@ -51,6 +51,7 @@ def _load():
     lib.h2o_oracle_free.restype = None
     lib.h2o_oracle_prefill.argtypes = [P, D, D, D, ctypes.c_int, D, D]
     lib.h2o_oracle_load_and_select.argtypes = [P, D, D, D, ctypes.c_int]
+    lib.h2o_oracle_prefill_chunk.argtypes = [P, D, D, D, ctypes.c_int, D, D]
     lib.h2o_oracle_decode.argtypes = [P, D, D, D, D, I, D, D]
     lib.h2o_oracle_resync.argtypes = [P, ctypes.c_int, ctypes.c_int]
     lib.h2o_oracle_set_policy.argtypes = [P, ctypes.c_int]
@@ -129,6 +130,21 @@ class OracleHead:
                                           _dp(attn) if want_attn else None)
         if rc != 0:
             raise RuntimeError("oracle prefill failed (state or capacity)")
+        return col, attn
+
+    def prefill_chunk(self, Q, K, V, want_attn: bool = False):
+        """The next m prompt tokens as one chunk (attend to cache + causally to the
+        chunk, accumulate, compress).  Returns (the chunk's column sums by position,
+        float64[t + m], attention outputs [m, d] or None)."""
+        Q, K, V = _f64(Q), _f64(K), _f64(V)
+        m = Q.shape[0]
+        assert Q.shape == K.shape == V.shape == (m, self.d)
+        col = np.empty(self.t + m, dtype=np.float64)
+        attn = np.empty((m, self.d), dtype=np.float64) if want_attn else None
+        rc = self._lib.h2o_oracle_prefill_chunk(self._h, _dp(Q), _dp(K), _dp(V), m, _dp(col),
+                                                _dp(attn) if want_attn else None)
+        if rc != 0:
+            raise RuntimeError("oracle prefill_chunk failed (capacity)")
         return col, attn
 
     def load_and_select(self, K, V, score):

@@ -93,3 +93,50 @@ def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0
         sets.append(set(np.flatnonzero(member).tolist()))
     return dict(outs=np.array(outs), sets=sets, evicted=evicted, colsum=colsum,
                 attn_prompt=attn_prompt, acc=acc)
+
+
+def brute_chunked(Q, K, V, chunks, heavy, recent, scale, score_dtype=np.float64, policy=0):
+    """Chunked prompt processing on the whole sequence at once: `chunks` lists
+    the chunk lengths.  Every token of a chunk attends to the tokens kept so far
+    and, causally, to its own chunk; the chunk's column sums are added to the
+    scores; then the kept set is cut to the budget by SORTING (last `recent`
+    positions stay, of the rest the `heavy` best by (rank value, position)).
+    Returns outputs [N, d], the kept set after every chunk and the final scores."""
+    Q = np.asarray(Q, np.float64); K = np.asarray(K, np.float64); V = np.asarray(V, np.float64)
+    N, d = Q.shape
+    assert sum(chunks) == N
+    k = heavy + recent
+    S = scale * (Q @ K.T)
+    acc = np.zeros(N)
+    member = np.zeros(N, dtype=bool)
+    outs = np.zeros((N, d))
+    sets = []
+    t0 = 0
+    for m in chunks:
+        t1 = t0 + m
+        csum = np.zeros(N)
+        for i in range(t0, t1):
+            G = member.copy()
+            G[t0:i + 1] = True
+            row = np.where(G, S[i], -np.inf)
+            e = np.exp(row - row.max())
+            p = e / e.sum()
+            outs[i] = p @ V
+            csum += p
+        if score_dtype == np.float32:
+            acc = (acc.astype(np.float32) + csum.astype(np.float32)).astype(np.float64)
+        else:
+            acc = acc + csum
+        member[t0:t1] = True
+        if member.sum() > k:
+            members = np.flatnonzero(member).tolist()
+            window = [j for j in members if j >= t1 - recent]
+            older = [j for j in members if j < t1 - recent]
+            r = _rank(acc, older, t1 - 1, policy, score_dtype)
+            older.sort(key=lambda j: (r[j], j), reverse=True)
+            member[:] = False
+            member[window] = True
+            member[older[:heavy]] = True
+        sets.append(set(np.flatnonzero(member).tolist()))
+        t0 = t1
+    return dict(outs=outs, sets=sets, acc=acc)

@@ -419,3 +419,95 @@ def test_average_policy_uniform_attention_closed_form():
 def test_policy_argument_is_validated():
     with pytest.raises(ValueError):
         OracleHead(4, 2, 2, 1.0, cap=8, policy=2)
+
+
+# ------------------------------------------------------- chunked prompt processing
+from tests.brute import brute_chunked  # noqa: E402
+
+
+def run_chunked(Q, K, V, chunks, heavy, recent, scale, score_f32=False, policy=0):
+    N, d = Q.shape
+    o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=N, policy=policy)
+    outs, sets = np.zeros((N, d)), []
+    t0 = 0
+    for m in chunks:
+        _, attn = o.prefill_chunk(Q[t0:t0 + m], K[t0:t0 + m], V[t0:t0 + m], want_attn=True)
+        outs[t0:t0 + m] = attn
+        sets.append(set(o.resident()[0].tolist()))
+        t0 += m
+    return o, outs, sets
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("chunks,heavy,recent", [
+    ([5, 5, 5, 5], 3, 2), ([1, 7, 2, 9, 1], 2, 3), ([12, 8], 4, 0), ([3, 3, 3, 3, 3, 3], 0, 4),
+    ([20], 3, 3), ([2, 18], 5, 5), ([9, 1, 1, 1, 8], 1, 1),
+])
+@pytest.mark.parametrize("f32,policy", [(False, 0), (True, 0), (False, 1), (True, 1)])
+def test_chunked_matches_brute_force(seed, chunks, heavy, recent, f32, policy):
+    d = 4
+    N = sum(chunks)
+    Q, K, V = make_inputs(7000 + seed, N, d)
+    scale = 0.5
+    o, outs, sets = run_chunked(Q, K, V, chunks, heavy, recent, scale, f32, policy)
+    ref = brute_chunked(Q, K, V, chunks, heavy, recent, scale, np.float32 if f32 else np.float64, policy)
+    assert sets == ref["sets"]
+    np.testing.assert_allclose(outs, ref["outs"], rtol=1e-12, atol=1e-13)
+    pos, sc = o.resident()
+    if f32:
+        assert np.array_equal(sc, ref["acc"][pos])
+    else:
+        np.testing.assert_allclose(sc, ref["acc"][pos], rtol=1e-12, atol=1e-14)
+    k = heavy + recent
+    assert len(pos) == min(N, k)
+    assert set(range(N - min(recent, N), N)) <= set(pos.tolist())
+    # every softmax row sums to one: nothing is lost except what was evicted
+    assert o.queries == N
+    assert sc.sum() + o.evicted_mass == pytest.approx(N, rel=1e-6 if f32 else 1e-12)
+
+
+@pytest.mark.parametrize("f32", [False, True])
+def test_chunks_of_one_are_generation_steps(f32):
+    """Algorithm 1 end of the range: chunks of a single token give, bit for bit,
+    what the generation step gives (outputs, kept sets, scores)."""
+    d, N, heavy, recent = 4, 40, 4, 3
+    Q, K, V = make_inputs(81, N, d)
+    a = OracleHead(d, heavy, recent, 0.5, score_f32=f32, cap=N)
+    b = OracleHead(d, heavy, recent, 0.5, score_f32=f32, cap=N)
+    for t in range(N):
+        r = a.decode(Q[t], K[t], V[t])
+        _, attn = b.prefill_chunk(Q[t:t + 1], K[t:t + 1], V[t:t + 1], want_attn=True)
+        assert np.array_equal(attn[0], r.out)
+        pa, sa = a.resident(); pb, sb = b.resident()
+        assert np.array_equal(pa, pb) and np.array_equal(sa, sb)
+
+
+@pytest.mark.parametrize("f32", [False, True])
+def test_one_chunk_is_the_one_shot_prompt_phase(f32):
+    """App. A end of the range: a single chunk holding the whole prompt gives, bit
+    for bit, the one-shot prompt phase."""
+    d, n, heavy, recent = 4, 30, 5, 4
+    Q, K, V = make_inputs(82, n, d)
+    a = OracleHead(d, heavy, recent, 0.5, score_f32=f32, cap=n)
+    b = OracleHead(d, heavy, recent, 0.5, score_f32=f32, cap=n)
+    ca, aa = a.prefill(Q, K, V, want_attn=True)
+    cb, ab = b.prefill_chunk(Q, K, V, want_attn=True)
+    assert np.array_equal(ca, cb) and np.array_equal(aa, ab)
+    pa, sa = a.resident(); pb, sb = b.resident()
+    assert np.array_equal(pa, pb) and np.array_equal(sa, sb)
+    assert a.evicted_mass == b.evicted_mass
+
+
+def test_chunking_is_invisible_while_nothing_is_evicted():
+    """Budget >= sequence length: however the prompt is cut into chunks, outputs
+    are full causal attention and scores the full column sums."""
+    d, n = 4, 36
+    Q, K, V = make_inputs(83, n, d)
+    full = OracleHead(d, n, n, 0.5, cap=n)
+    col, attn = full.prefill(Q, K, V, want_attn=True)
+    for chunks in ([36], [1] * 36, [10, 1, 25], [17, 19]):
+        o, outs, _ = run_chunked(Q, K, V, chunks, n, n, 0.5)
+        np.testing.assert_allclose(outs, attn, rtol=1e-13, atol=1e-14)
+        pos, sc = o.resident()
+        assert pos.tolist() == list(range(n))
+        np.testing.assert_allclose(sc, col, rtol=1e-12, atol=1e-14)
