@@ -146,6 +146,34 @@ int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K,
                        const void *V, int32_t n, void *workspace,
                        size_t ws_bytes, float *colsum_out, void *hip_stream);
 
+/* Device bytes of scratch h2o_prefill_chunk needs for chunks of up to m tokens
+ * (cache + chunk as one candidate list: K and V rows, old scores, positions,
+ * column sums, row statistics).  Returns 0 for invalid arguments and when
+ * heavy + recent + m exceeds H2O_MAX_PROMPT. */
+size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m);
+
+/*
+ * The next m prompt tokens as one chunk: prompt processing with bounded memory.
+ * The paper gives the two ends of the range: token-by-token eviction over the
+ * whole sequence (Algorithm 1) and full attention over the prompt followed by
+ * one compression (App. A).  Here every token of the chunk attends to the
+ * tokens in the cache and, causally, to the chunk's own tokens (nothing is
+ * evicted inside a chunk); the column sums of these m softmax rows are added to
+ * the accumulated scores (Algorithm 2's accumulate line; binary32 add of the
+ * binary32 column sum); then cache + chunk are compressed to the budget by the
+ * prompt rule of h2o_prefill_select (last `recent` positions, `heavy` best older
+ * ones).  m = 1 is what h2o_decode_step computes (without the output); one
+ * chunk holding the whole prompt on an empty cache is h2o_prefill_scores.
+ *   Q, K, V   [batch, heads, m, head_dim] in cfg.dtype
+ *   workspace >= h2o_prefill_chunk_workspace_bytes(cfg, m)
+ * The cached tokens must sit in ascending position order, which holds after
+ * h2o_cache_init / _reset / h2o_prefill_* and until a generation step evicts.
+ * Then t becomes t + m.  Errors: EINVAL, EUNSUPPORTED, ENOMEM, ESTATE (slots no
+ * longer in position order), EHIP.
+ */
+int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void *V,
+                      int32_t m, void *workspace, size_t ws_bytes, void *hip_stream);
+
 /*
  * Device bytes of scratch h2o_prefill_attention / h2o_prefill_attention_scores
  * need for a prompt of n tokens (a transposed copy of V padded to whole tiles,

@@ -29,7 +29,8 @@ EXPORTS = (
     "h2o_cache_destroy", "h2o_prefill_colsum", "h2o_prefill_select", "h2o_prefill_scores",
     "h2o_decode_step", "h2o_cache_snapshot", "h2o_cache_restore", "h2o_cache_tokens_seen",
     "h2o_cache_regions", "h2o_status_str", "h2o_prefill_attention_workspace_bytes",
-    "h2o_prefill_attention", "h2o_prefill_attention_scores",
+    "h2o_prefill_attention", "h2o_prefill_attention_scores", "h2o_prefill_chunk_workspace_bytes",
+    "h2o_prefill_chunk",
 )
 
 
@@ -67,6 +68,9 @@ _lib.h2o_prefill_attention_workspace_bytes.restype = _sz
 _lib.h2o_prefill_attention_workspace_bytes.argtypes = [_cfgp, _i32]
 _lib.h2o_prefill_attention.argtypes = [_cfgp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp, _vp]
 _lib.h2o_prefill_attention_scores.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp, _vp]
+_lib.h2o_prefill_chunk_workspace_bytes.restype = _sz
+_lib.h2o_prefill_chunk_workspace_bytes.argtypes = [_cfgp, _i32]
+_lib.h2o_prefill_chunk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
 _lib.h2o_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.h2o_cache_snapshot.argtypes = [_vp, _vp, _vp, _vp]
 _lib.h2o_cache_restore.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
@@ -166,6 +170,15 @@ def h2o_prefill_attention_scores(cache, Q, K, V, n, workspace, ws_bytes, out, co
                                              _ptr(workspace), int(ws_bytes), _ptr(out),
                                              _ptr(colsum_out), _stream(stream)),
            "h2o_prefill_attention_scores")
+
+
+def h2o_prefill_chunk_workspace_bytes(cfg: h2o_config, m: int) -> int:
+    return int(_lib.h2o_prefill_chunk_workspace_bytes(ctypes.byref(cfg), int(m)))
+
+
+def h2o_prefill_chunk(cache, Q, K, V, m, workspace, ws_bytes, stream=None) -> None:
+    _check(_lib.h2o_prefill_chunk(cache, _ptr(Q), _ptr(K), _ptr(V), int(m), _ptr(workspace),
+                                  int(ws_bytes), _stream(stream)), "h2o_prefill_chunk")
 
 
 def h2o_decode_step(cache, q, k_new, v_new, out, stream=None) -> None:

@@ -72,6 +72,7 @@ int h2o_cache_init(const h2o_config *cfg, void *dev_mem, size_t bytes, void *hip
     c->k = cfg->heavy + cfg->recent;
     c->esize = h2o_esize(cfg->dtype);
     c->t = 0;
+    c->sorted = true;
     char *base = static_cast<char *>(dev_mem);
     c->K = base;
     c->V = base + l.kv;
@@ -90,6 +91,7 @@ int h2o_cache_reset(h2o_cache *cache, void *hip_stream)
     const hipError_t e = h2o_launch_mark_free(*cache, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return H2O_EHIP;
     cache->t = 0;
+    cache->sorted = true;
     return H2O_OK;
 }
 
@@ -108,9 +110,9 @@ int h2o_prefill_colsum(const h2o_config *cfg, const void *Q, const void *K, int3
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     float *lse = static_cast<float *>(workspace);
     const double scale = h2o_scale_of(*cfg);
-    hipError_t e = h2o_launch_prefill_lse(*cfg, scale, Q, K, n, lse, st);
+    hipError_t e = h2o_launch_prefill_lse(*cfg, scale, Q, K, n, n, lse, st);
     if (e != hipSuccess) return H2O_EHIP;
-    e = h2o_launch_prefill_colsum(*cfg, scale, Q, K, n, lse, colsum_out, st);
+    e = h2o_launch_prefill_colsum(*cfg, scale, Q, K, n, n, lse, colsum_out, st);
     return hip_rc(e);
 }
 
@@ -122,9 +124,11 @@ int h2o_prefill_select(h2o_cache *cache, const void *K, const void *V, const flo
     if (n > H2O_MAX_PROMPT) return H2O_EUNSUPPORTED;
     if (cache->t != 0) return H2O_ESTATE;
     const hipError_t e =
-        h2o_launch_select_gather(*cache, K, V, score, n, static_cast<hipStream_t>(hip_stream));
+        h2o_launch_select_gather(*cache, K, V, score, nullptr, nullptr, n, n,
+                                 static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return H2O_EHIP;
     cache->t = n;
+    cache->sorted = true;
     return H2O_OK;
 }
 
@@ -184,9 +188,56 @@ int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K,
     const size_t half = h2o_prefill_workspace_bytes(cfg, n) / 2;
     float *lse2 = reinterpret_cast<float *>(ws + align_up(h2o_attn_vt_bytes(*cfg, n), 256));
     float *sums = colsum_out ? colsum_out : reinterpret_cast<float *>(reinterpret_cast<char *>(lse2) + half);
-    const hipError_t e = h2o_launch_prefill_colsum(*cfg, h2o_scale_of(*cfg), Q, K, n, lse2, sums, st);
+    const hipError_t e = h2o_launch_prefill_colsum(*cfg, h2o_scale_of(*cfg), Q, K, n, n, lse2, sums, st);
     if (e != hipSuccess) return H2O_EHIP;
     return h2o_prefill_select(cache, K, V, sums, n, hip_stream);
+}
+
+size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m)
+{
+    if (check_config(cfg) != H2O_OK || m < 1) return 0;
+    const size_t k = (size_t)cfg->heavy + cfg->recent;
+    if (k + (size_t)m > H2O_MAX_PROMPT) return 0;
+    const size_t heads = (size_t)cfg->batch * cfg->heads, ncat = k + m;
+    const size_t rows = align_up(heads * ncat * cfg->head_dim * h2o_esize(cfg->dtype), 256);
+    const size_t vec = align_up(heads * ncat * sizeof(float), 256);
+    // K and V of cache + chunk, old scores, positions, column sums, row statistics
+    return 2 * rows + 3 * vec + align_up(heads * (size_t)m * sizeof(float), 256);
+}
+
+int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void *V, int32_t m,
+                      void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    if (!cache || !Q || !K || !V || !workspace || m < 1) return H2O_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(workspace)) return H2O_EINVAL;
+    if (!cache->sorted) return H2O_ESTATE;
+    const h2o_config &cfg = cache->cfg;
+    const int occ = cache->t < cache->k ? cache->t : cache->k;
+    if ((int64_t)cache->k + m > H2O_MAX_PROMPT || (int64_t)cache->t + m >= 0x7ffffff0) return H2O_EUNSUPPORTED;
+    if (ws_bytes < h2o_prefill_chunk_workspace_bytes(&cfg, m)) return H2O_ENOMEM;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const size_t heads = (size_t)cfg.batch * cfg.heads, ncat_max = (size_t)cache->k + m;
+    const size_t rows = align_up(heads * ncat_max * cfg.head_dim * cache->esize, 256);
+    const size_t vec = align_up(heads * ncat_max * sizeof(float), 256);
+    char *ws = static_cast<char *>(workspace);
+    char *Kcat = ws, *Vcat = ws + rows;
+    float *base = reinterpret_cast<float *>(ws + 2 * rows);
+    int32_t *pos_cat = reinterpret_cast<int32_t *>(ws + 2 * rows + vec);
+    float *colsum = reinterpret_cast<float *>(ws + 2 * rows + 2 * vec);
+    float *lse = reinterpret_cast<float *>(ws + 2 * rows + 3 * vec);
+    const int ncat = occ + m;
+    const double scale = h2o_scale_of(cfg);
+    hipError_t e = h2o_launch_concat(*cache, K, V, m, occ, Kcat, Vcat, base, pos_cat, st);
+    if (e != hipSuccess) return H2O_EHIP;
+    e = h2o_launch_prefill_lse(cfg, scale, Q, Kcat, m, ncat, lse, st);
+    if (e != hipSuccess) return H2O_EHIP;
+    e = h2o_launch_prefill_colsum(cfg, scale, Q, Kcat, m, ncat, lse, colsum, st);
+    if (e != hipSuccess) return H2O_EHIP;
+    e = h2o_launch_select_gather(*cache, Kcat, Vcat, colsum, base, pos_cat, ncat, cache->t + m, st);
+    if (e != hipSuccess) return H2O_EHIP;
+    cache->t += m;
+    cache->sorted = true;
+    return H2O_OK;
 }
 
 int h2o_decode_step(h2o_cache *cache, const void *q, const void *k_new, const void *v_new,
@@ -199,6 +250,9 @@ int h2o_decode_step(h2o_cache *cache, const void *q, const void *k_new, const vo
     const hipError_t e =
         h2o_launch_decode(*cache, q, k_new, v_new, out, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return H2O_EHIP;
+    // free slots fill in index order (positions stay ascending); an eviction
+    // overwrites a slot in the middle
+    if (cache->t >= cache->k) cache->sorted = false;
     cache->t += 1;
     return H2O_OK;
 }
@@ -229,6 +283,7 @@ int h2o_cache_restore(h2o_cache *cache, const void *K, const void *V, const floa
         hipMemcpyAsync(cache->pos, pos, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, st) != hipSuccess)
         return H2O_EHIP;
     cache->t = tokens_seen;
+    cache->sorted = false;      // not known
     return H2O_OK;
 }
 

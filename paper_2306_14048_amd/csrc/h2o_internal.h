@@ -11,6 +11,7 @@ struct h2o_cache {
     int k;             // heavy + recent
     int esize;         // bytes per element of K/V
     int t;             // tokens seen so far
+    bool sorted;       // occupied slots hold ascending positions (true until a step evicts)
     char *K;           // [B*Hh][k][d]
     char *V;           // [B*Hh][k][d]
     float *acc;        // [B*Hh][k]
@@ -28,11 +29,13 @@ static inline double h2o_scale_of(const h2o_config &c)
 hipError_t h2o_launch_mark_free(const h2o_cache &c, hipStream_t st);
 hipError_t h2o_launch_decode(const h2o_cache &c, const void *q, const void *k_new,
                              const void *v_new, void *out, hipStream_t st);
+// prompt scoring: the nq queries (rows of Q) are the last nq positions of the nk
+// keys; lse [B*Hh][nq] = log2 of the row normalisers, colsum [B*Hh][nk]
 hipError_t h2o_launch_prefill_lse(const h2o_config &cfg, double scale, const void *Q,
-                                  const void *K, int n, float *lse, hipStream_t st);
+                                  const void *K, int nq, int nk, float *lse, hipStream_t st);
 hipError_t h2o_launch_prefill_colsum(const h2o_config &cfg, double scale, const void *Q,
-                                     const void *K, int n, const float *lse, float *colsum,
-                                     hipStream_t st);
+                                     const void *K, int nq, int nk, const float *lse,
+                                     float *colsum, hipStream_t st);
 // causal attention over the prompt: V is transposed into `vt` (h2o_attn_vt_bytes
 // bytes), `lse2` receives log2 of every row's normaliser of exp2(scale*log2(e)*<q,k>),
 // `lse_nat` (nullable) the natural-log row log-sum-exp; 16-bit element types only
@@ -40,8 +43,14 @@ size_t h2o_attn_vt_bytes(const h2o_config &cfg, int n);
 hipError_t h2o_launch_prefill_attention(const h2o_config &cfg, double scale, const void *Q,
                                         const void *K, const void *V, int n, void *vt,
                                         float *lse2, float *lse_nat, void *out, hipStream_t st);
+// compression of n candidates per head (entry j: position pos_in[j] or j, score
+// base[j] + score[j] or score[j]) into the cache; t_new = tokens seen afterwards
 hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const void *V,
-                                    const float *score, int n, hipStream_t st);
+                                    const float *score, const float *base, const int32_t *pos_in,
+                                    int n, int t_new, hipStream_t st);
+// the n_occ cached tokens followed by the m chunk tokens as one candidate list
+hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn, int m, int n_occ,
+                             void *Kcat, void *Vcat, float *base, int32_t *pos_cat, hipStream_t st);
 
 // ---- element types ----------------------------------------------------------
 // Raw storage views: f32 -> float, f16 -> _Float16, bf16 -> uint16_t bit pattern.

@@ -118,7 +118,7 @@ constexpr int NLB = 4;         // row-statistic buffers (pass 2; read one phase 
 // phase ("ping-pong").  s_setprio lets the matrix phase win the issue slot.
 template <int DT, int D, int MB, bool COLSUM>
 __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
-    const char *__restrict__ Qg, const char *__restrict__ Kg, int n, int heads, float c2,
+    const char *__restrict__ Qg, const char *__restrict__ Kg, int nq, int nk, int heads, float c2,
     float *__restrict__ lse2, float *__restrict__ colsum)
 {
     constexpr int ES = DT == H2O_F32 ? 4 : 2;
@@ -152,7 +152,13 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int grp = wave >> 2;            // ping-pong group
-    const int nblk = (n + SROWS - 1) / SROWS;
+    // The nq queries are the LAST nq positions of the nk keys (nq == nk for a whole
+    // prompt; nq < nk when a chunk of new tokens attends to nk - nq cached tokens in
+    // front of it): query row i sits at key position off + i and sees keys <= off + i.
+    const int off = nk - nq;
+    const int ns = COLSUM ? nk : nq;      // stationary rows
+    const int nt = COLSUM ? nq : nk;      // streamed rows
+    const int nblk = (ns + SROWS - 1) / SROWS;
     // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD
     // has its own L2.  All blocks of a head share the streamed operand, so a head
     // lives on ONE XCD (ids that agree modulo 8) and its blocks run close together
@@ -171,31 +177,32 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     // pass 2's first key block sees every query tile
     const int blk = COLSUM ? ord : nblk - 1 - ord;
     const int s0 = blk * SROWS;
-    const size_t hbase = (size_t)head * n * ROWB;
-    const char *Sg = (COLSUM ? Kg : Qg) + hbase;     // stationary operand
-    const char *Tg = (COLSUM ? Qg : Kg) + hbase;     // streamed operand
+    const char *Sg = (COLSUM ? Kg : Qg) + (size_t)head * ns * ROWB;     // stationary operand
+    const char *Tg = (COLSUM ? Qg : Kg) + (size_t)head * nt * ROWB;     // streamed operand
 
     const int srow = s0 + wave * 32 + l32;           // this lane's stationary row
-    // Rows past n are clamped to row n-1 (in bounds) and zeroed after arrival.
+    // Rows past the end are clamped to the last row (in bounds) and zeroed after arrival.
     uint4 st[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f)
-        st[f] = *reinterpret_cast<const uint4 *>(Sg + (size_t)min(srow, n - 1) * ROWB + (2 * f + half) * 16);
-    if (srow >= n) {
+        st[f] = *reinterpret_cast<const uint4 *>(Sg + (size_t)min(srow, ns - 1) * ROWB + (2 * f + half) * 16);
+    if (srow >= ns) {
 #pragma unroll
         for (int f = 0; f < NF; ++f) st[f] = make_uint4(0, 0, 0, 0);
     }
 
-    const int ntile_all = (n + BN - 1) / BN;
-    const int t_begin = COLSUM ? s0 / BN : 0;
-    const int t_end = COLSUM ? ntile_all : min(ntile_all, (s0 + SROWS) / BN);
+    const int ntile_all = (nt + BN - 1) / BN;
+    // pass 1 streams the keys its last query can see; pass 2 streams the queries
+    // from the first one that sees this block's first key
+    const int t_begin = COLSUM ? max(0, s0 - off) / BN : 0;
+    const int t_end = COLSUM ? ntile_all : min(ntile_all, (off + s0 + SROWS + BN - 1) / BN);
 
     // Staging of a streamed tile: copy instruction c of wave w fills LDS chunks
     // [(c*NWV + w)*64, +64) of the buffer; lane l's chunk q = that base + l sits in
     // tile row q / CPR at position q % CPR and comes from global chunk
     // (q % CPR) ^ key(row).  A head's operand is < 4 GiB: a 32-bit per-lane offset
-    // inside the tile plus the tile's wave-uniform offset.  Rows past n (only in a
-    // ragged last tile) are clamped to row n-1; what they hold is never used
+    // inside the tile plus the tile's wave-uniform offset.  Rows past the end (only in a
+    // ragged last tile) are clamped to the last row; what they hold is never used
     // (both passes mask them).  Pass 2 also copies the tile's BN row statistics,
     // LPW lanes of every wave taking LPW of them, so that every wave issues the
     // same number of copy instructions per tile and one wait count fits all.
@@ -207,18 +214,18 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
         goff[c] = r * ROWB;
         gchunk[c] = ((pos ^ ((r >> RSH) & KMASK)) * 16u);
     }
-    const i32x4 rsrc = make_rsrc(Tg, (unsigned)n * ROWB);
-    const i32x4 rsrc_lse = make_rsrc(lse2 + (size_t)head * n, (unsigned)n * 4u);
+    const i32x4 rsrc = make_rsrc(Tg, (unsigned)nt * ROWB);
+    const i32x4 rsrc_lse = make_rsrc(lse2 + (size_t)head * nq, (unsigned)nq * 4u);
     // the low 32 bits of a generic pointer into LDS are the LDS byte offset
     const unsigned lds_w = __builtin_amdgcn_readfirstlane(
         (unsigned)reinterpret_cast<size_t>(tile_l) + wave * 1024);
     const unsigned lds_lse = (unsigned)reinterpret_cast<size_t>(lse_l);
-    const unsigned last_row_off = (unsigned)(n - 1) * ROWB;
+    const unsigned last_row_off = (unsigned)(nt - 1) * ROWB;
     const bool lse_lane = lane / LPW == wave;        // (lane < BN follows from wave < NWV)
     // i = index of the tile in this block's sequence (selects the buffers)
     auto fetch = [&](int tile, int tb, int lb) {
         const unsigned t0 = (unsigned)tile * (BN * ROWB);
-        if (t0 + BN * ROWB <= (unsigned)n * ROWB) {            // whole tile inside the operand
+        if (t0 + BN * ROWB <= (unsigned)nt * ROWB) {           // whole tile inside the operand
 #pragma unroll
             for (int c = 0; c < CPT; ++c)
                 dma16(rsrc, goff[c] + gchunk[c], t0, lds_w + tb * TILEB + c * NWV * 1024);
@@ -229,7 +236,7 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                       lds_w + tb * TILEB + c * NWV * 1024);
         }
         if constexpr (COLSUM) {
-            // lane l writes LDS word l of the buffer; statistics past n read as 0
+            // lane l writes LDS word l of the buffer; statistics past nq read as 0
             // (end of the descriptor) or as the next head's and are masked later
             if (lse_lane) dma4(rsrc_lse, (unsigned)lane * 4u, (unsigned)tile * (BN * 4u), lds_lse + lb * (BN * 4));
         }
@@ -238,7 +245,7 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
     float m_run = -INFINITY, l_run = 0.f;   // pass 1: running max / sum (base 2)
     float c_run = 0.f;                      // pass 2: running column sum
 
-    // Every block has at least one tile (s0 < n).  The first two are requested
+    // Every block has at least one tile.  The first two are requested
     // here; waiting for the first also completes the stationary loads above
     // (vector loads finish in order).  Requests past the block's last tile repeat
     // that tile (harmless, keeps the request count per iteration constant).
@@ -276,9 +283,9 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
         fetch(min(tile + 2, t_end - 1), tb2, (lb + 2) & (NLB - 1));
         const int r0 = tile * BN;
         const int w0 = s0 + wave * 32;            // first stationary row of this wave
-        // pass 1: keys r0.. are visible to queries >= r0; pass 2: queries up to
-        // r0+BN-1 see keys <= r0+BN-1
-        const bool live = !MASKED || (COLSUM ? r0 + BN - 1 >= w0 : r0 <= w0 + 31);
+        // pass 1: keys r0.. are visible to the queries at positions >= r0; pass 2:
+        // the queries up to position off+r0+BN-1 see the keys up to there
+        const bool live = !MASKED || (COLSUM ? off + r0 + BN - 1 >= w0 : r0 <= off + w0 + 31);
         f32x16 acc[MB];
         if (live) {
             __builtin_amdgcn_s_setprio(2);
@@ -304,7 +311,8 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
 
         if (live) {
             if constexpr (!COLSUM) {
-                // streamed rows are keys j, this lane's row is query i = srow: need j <= i.
+                // streamed rows are keys j, this lane's row is the query at position
+                // off + srow: need j <= off + srow.
                 // m_run tracks the maximum of the raw products (c2 > 0 keeps the order);
                 // the scale is folded into the exponent's fma
                 if constexpr (MASKED) {
@@ -313,7 +321,7 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                            if (j > srow) acc[mb][v] = -INFINITY;
+                            if (j > off + srow) acc[mb][v] = -INFINITY;
                         }
                 }
                 float mx = m_run;
@@ -334,8 +342,8 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                 l_run = l_run * __builtin_amdgcn_exp2f((m_run - ms) * c2) + (sum0 + sum1);
                 m_run = mx;
             } else {
-                // streamed rows are queries i, this lane's row is key j = srow: need
-                // j <= i < n
+                // streamed rows are queries i (at position off + i), this lane's row is
+                // key j = srow: need j <= off + i, i < nq
                 const float *ll = lse_l + lb * BN;
                 float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
@@ -352,7 +360,7 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 const int i = r0 + mb * 32 + 8 * gq + 4 * half + e;
-                                if (i < srow || i >= n) x[e] = -INFINITY;
+                                if (off + i < srow || i >= nq) x[e] = -INFINITY;
                             }
                         }
                         sum0 += __builtin_amdgcn_exp2f(x[0]) + __builtin_amdgcn_exp2f(x[2]);
@@ -366,16 +374,18 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
         dma_wait_upto<CPF>();
         wg_barrier();
     };
-    // SROWS is a multiple of BN, so the tiles that touch the diagonal are exactly
-    // those that overlap this workgroup's own rows [s0, s0 + SROWS)
+    // Tiles that need the mask: in pass 1 from the first key tile that reaches past
+    // the position of this block's first query; in pass 2 up to the last query tile
+    // that does not yet see this block's last key.
     if constexpr (!COLSUM) {
-        const int t_diag0 = s0 / BN;
+        const int t_diag0 = min(t_end, (off + s0 + 1) / BN);
         for (int tile = t_begin; tile < t_diag0; ++tile) tile_step(tile, std::false_type{});
         for (int tile = t_diag0; tile < t_end; ++tile) tile_step(tile, std::true_type{});
     } else {
-        const int t_diag1 = min(t_end, (s0 + SROWS) / BN);
-        // a ragged last tile holds rows past n: it takes the masking path as well
-        const int t_rag = (n % BN) ? max(t_diag1, t_end - 1) : t_end;
+        const int x = s0 + SROWS - 1 - off;      // first query (local) that sees the whole block
+        const int t_diag1 = min(t_end, max(t_begin, x > 0 ? (x + BN - 1) / BN : 0));
+        // a ragged last tile holds rows past nq: it takes the masking path as well
+        const int t_rag = (nq % BN) ? max(t_diag1, t_end - 1) : t_end;
         for (int tile = t_begin; tile < t_diag1; ++tile) tile_step(tile, std::true_type{});
         for (int tile = t_diag1; tile < t_rag; ++tile) tile_step(tile, std::false_type{});
         for (int tile = t_rag; tile < t_end; ++tile) tile_step(tile, std::true_type{});
@@ -388,16 +398,16 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
         const float M = fmaxf(m_run, m2);            // finite: key 0 is visible to every query
         const float L = l_run * __builtin_amdgcn_exp2f((m_run - M) * c2) +
                         l2 * __builtin_amdgcn_exp2f((m2 - M) * c2);
-        if (half == 0 && srow < n) lse2[(size_t)head * n + srow] = M * c2 + __builtin_amdgcn_logf(L);
+        if (half == 0 && srow < nq) lse2[(size_t)head * nq + srow] = M * c2 + __builtin_amdgcn_logf(L);
     } else {
         const float c = c_run + __shfl_xor(c_run, 32, 64);
-        if (half == 0 && srow < n) colsum[(size_t)head * n + srow] = c;
+        if (half == 0 && srow < nk) colsum[(size_t)head * nk + srow] = c;
     }
 }
 
 template <int DT, int D, bool COLSUM>
-hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
-                       float *lse2, float *colsum, hipStream_t st)
+hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const void *K, int nq,
+                       int nk, float *lse2, float *colsum, hipStream_t st)
 {
     constexpr int SROWS = NWV * 32;
     constexpr int ES = DT == H2O_F32 ? 4 : 2;
@@ -405,7 +415,7 @@ hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const
     constexpr int BN = 32 * MB;
     constexpr size_t smem = NTB * (size_t)BN * (D * ES) + NLB * BN * sizeof(float);
     const int heads = cfg.batch * cfg.heads;
-    const int nblk = (n + SROWS - 1) / SROWS;
+    const int nblk = ((COLSUM ? nk : nq) + SROWS - 1) / SROWS;
     const float c2 = (float)(scale * 1.4426950408889634);
     auto kern = prefill_pass_kernel<DT, D, MB, COLSUM>;
     if (smem > 48 * 1024) {
@@ -420,39 +430,39 @@ hipError_t launch_pass(const h2o_config &cfg, double scale, const void *Q, const
     hipLaunchKernelGGL(kern,
                        dim3((unsigned)((heads + 63) / 64) * 64 * nblk),
                        dim3(NWV * 64), smem, st, static_cast<const char *>(Q),
-                       static_cast<const char *>(K), n, heads, c2, lse2, colsum);
+                       static_cast<const char *>(K), nq, nk, heads, c2, lse2, colsum);
     return hipGetLastError();
 }
 
 template <bool COLSUM>
-hipError_t dispatch(const h2o_config &cfg, double scale, const void *Q, const void *K, int n,
-                    float *lse2, float *colsum, hipStream_t st)
+hipError_t dispatch(const h2o_config &cfg, double scale, const void *Q, const void *K, int nq,
+                    int nk, float *lse2, float *colsum, hipStream_t st)
 {
     const int d = cfg.head_dim;
     switch (cfg.dtype) {
     case H2O_F32:
-        return d == 64 ? launch_pass<H2O_F32, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_F32, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_F32, 64, COLSUM>(cfg, scale, Q, K, nq, nk, lse2, colsum, st)
+                       : launch_pass<H2O_F32, 128, COLSUM>(cfg, scale, Q, K, nq, nk, lse2, colsum, st);
     case H2O_F16:
-        return d == 64 ? launch_pass<H2O_F16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_F16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_F16, 64, COLSUM>(cfg, scale, Q, K, nq, nk, lse2, colsum, st)
+                       : launch_pass<H2O_F16, 128, COLSUM>(cfg, scale, Q, K, nq, nk, lse2, colsum, st);
     default:
-        return d == 64 ? launch_pass<H2O_BF16, 64, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st)
-                       : launch_pass<H2O_BF16, 128, COLSUM>(cfg, scale, Q, K, n, lse2, colsum, st);
+        return d == 64 ? launch_pass<H2O_BF16, 64, COLSUM>(cfg, scale, Q, K, nq, nk, lse2, colsum, st)
+                       : launch_pass<H2O_BF16, 128, COLSUM>(cfg, scale, Q, K, nq, nk, lse2, colsum, st);
     }
 }
 
 }  // namespace
 
 hipError_t h2o_launch_prefill_lse(const h2o_config &cfg, double scale, const void *Q,
-                                  const void *K, int n, float *lse, hipStream_t st)
+                                  const void *K, int nq, int nk, float *lse, hipStream_t st)
 {
-    return dispatch<false>(cfg, scale, Q, K, n, lse, nullptr, st);
+    return dispatch<false>(cfg, scale, Q, K, nq, nk, lse, nullptr, st);
 }
 
 hipError_t h2o_launch_prefill_colsum(const h2o_config &cfg, double scale, const void *Q,
-                                     const void *K, int n, const float *lse, float *colsum,
-                                     hipStream_t st)
+                                     const void *K, int nq, int nk, const float *lse,
+                                     float *colsum, hipStream_t st)
 {
-    return dispatch<true>(cfg, scale, Q, K, n, const_cast<float *>(lse), colsum, st);
+    return dispatch<true>(cfg, scale, Q, K, nq, nk, const_cast<float *>(lse), colsum, st);
 }

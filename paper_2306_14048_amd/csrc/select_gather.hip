@@ -48,10 +48,14 @@ __device__ inline int block_exclusive_scan(int v, int *scratch, int &total)
     return base + inc - v;
 }
 
+// Entry j of a head's n candidates is the token at position pos_in[j] (ascending;
+// pos_in == nullptr: position j) with score base[j] + score[j] (base == nullptr:
+// score[j]); t_new = number of tokens seen once these are stored.
 template <int ROWB>
 __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     const char *__restrict__ Kp, const char *__restrict__ Vp, const float *__restrict__ score,
-    int n, char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
+    const float *__restrict__ base, const int32_t *__restrict__ pos_in, int n, int t_new,
+    char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, int k, int heavy, int recent, int rank)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -61,13 +65,18 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     __shared__ int scan_l[SG_NW + 1];
 
     const int head = blockIdx.x, tid = threadIdx.x;
-    const float *sc = score + (size_t)head * n;
+    const float *sc_in = score + (size_t)head * n;
+    const float *bs = base ? base + (size_t)head * n : nullptr;
+    const int32_t *pin = pos_in ? pos_in + (size_t)head * n : nullptr;
     const size_t hoff = (size_t)head * k;
+    // the score of entry j as it will be stored, and its position
+    auto sc_of = [&](int j) { return bs ? bs[j] + sc_in[j] : sc_in[j]; };
+    auto pos_of = [&](int j) { return pin ? pin[j] : j; };
 
     // what ranks an older token: its score, or (averaged ranking) its score over
     // the n - j prompt queries that scored it
     auto ranked = [&](float v, int j) {
-        return rank == H2O_RANK_AVERAGED ? __fdiv_rn(v, (float)(n - j)) : v;
+        return rank == H2O_RANK_AVERAGED ? __fdiv_rn(v, (float)(t_new - pos_of(j))) : v;
     };
 
     for (int s = tid; s < k; s += SG_NT) sel_l[s] = -1;
@@ -76,9 +85,19 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
         __syncthreads();
         for (int s = tid; s < n; s += SG_NT) sel_l[s] = s;
     } else {
-        const int older = n - recent;                  // candidates: positions [0, older)
+        // candidates: the entries in front of the window of the last `recent`
+        // positions; positions ascend, so they are a prefix [0, older)
+        int older = n - recent;
+        if (pin) {
+            int cnt = 0;
+            for (int j = tid; j < n; j += SG_NT) cnt += pin[j] < t_new - recent;
+            int total;
+            block_exclusive_scan(cnt, scan_l, total);
+            older = total;
+            __syncthreads();
+        }
         unsigned thr = 0, need = 0;                    // keep keys > thr, and `need` of those == thr
-        if (heavy > 0) {
+        if (heavy > 0 && older > heavy) {
             // radix select: the heavy-th largest key among the older tokens
             unsigned prefix = 0, mask = 0;
             need = (unsigned)heavy;
@@ -86,7 +105,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
                 for (int b = tid; b < 256; b += SG_NT) hist[b] = 0;
                 __syncthreads();
                 for (int j = tid; j < older; j += SG_NT) {
-                    const unsigned key = order_key(ranked(sc[j], j));
+                    const unsigned key = order_key(ranked(sc_of(j), j));
                     if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
                 }
                 __syncthreads();
@@ -115,7 +134,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
         const int j0 = min(n, tid * per), j1 = min(n, j0 + per);
         int eq_cnt = 0;
         if (heavy > 0)
-            for (int j = j0; j < min(j1, older); ++j) eq_cnt += order_key(ranked(sc[j], j)) == thr;
+            for (int j = j0; j < min(j1, older); ++j) eq_cnt += order_key(ranked(sc_of(j), j)) == thr;
         int eq_total;
         int eq_before = block_exclusive_scan(eq_cnt, scan_l, eq_total);
         // among equal scores the higher positions are kept: the last `need` of them
@@ -126,7 +145,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
             for (int j = j0; j < j1; ++j) {
                 bool keep = j >= older;
                 if (!keep && heavy > 0) {
-                    const unsigned key = order_key(ranked(sc[j], j));
+                    const unsigned key = order_key(ranked(sc_of(j), j));
                     if (key > thr) keep = true;
                     else if (key == thr) { keep = e >= eq_first_kept; ++e; }
                 }
@@ -140,7 +159,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
             for (int j = j0; j < j1; ++j) {
                 bool keep = j >= older;
                 if (!keep && heavy > 0) {
-                    const unsigned key = order_key(ranked(sc[j], j));
+                    const unsigned key = order_key(ranked(sc_of(j), j));
                     if (key > thr) keep = true;
                     else if (key == thr) { keep = e >= eq_first_kept; ++e; }
                 }
@@ -153,8 +172,8 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     // bookkeeping of every slot
     for (int s = tid; s < k; s += SG_NT) {
         const int j = sel_l[s];
-        pos_g[hoff + s] = j;
-        acc_g[hoff + s] = j >= 0 ? sc[j] : 0.f;
+        pos_g[hoff + s] = j >= 0 ? pos_of(j) : -1;
+        acc_g[hoff + s] = j >= 0 ? sc_of(j) : 0.f;
     }
     // gather rows: LPR lanes copy one row of ROWB bytes
     constexpr int LPR = ROWB / 16;
@@ -203,7 +222,8 @@ hipError_t h2o_launch_mark_free(const h2o_cache &c, hipStream_t st)
 }
 
 hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const void *V,
-                                    const float *score, int n, hipStream_t st)
+                                    const float *score, const float *base, const int32_t *pos_in,
+                                    int n, int t_new, hipStream_t st)
 {
     const int heads = c.cfg.batch * c.cfg.heads;
     const int rowb = c.cfg.head_dim * c.esize;
@@ -211,7 +231,8 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
     const char *Kp = static_cast<const char *>(K), *Vp = static_cast<const char *>(V);
 #define H2O_SG(RB)                                                                              \
     hipLaunchKernelGGL((select_gather_kernel<RB>), dim3(heads), dim3(SG_NT), smem, st, Kp, Vp,   \
-                       score, n, c.K, c.V, c.acc, c.pos, c.k, c.cfg.heavy, c.cfg.recent, c.cfg.rank)
+                       score, base, pos_in, n, t_new, c.K, c.V, c.acc, c.pos, c.k, c.cfg.heavy, \
+                       c.cfg.recent, c.cfg.rank)
     switch (rowb) {
     case 128: H2O_SG(128); break;
     case 256: H2O_SG(256); break;
@@ -219,5 +240,56 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
     default: return hipErrorInvalidValue;
     }
 #undef H2O_SG
+    return hipGetLastError();
+}
+
+// ---- cache + chunk -> one candidate list per head ---------------------------------
+//
+// Chunked prompt processing treats the n_occ cached tokens (slots in ascending
+// position order) followed by the m tokens of the chunk as one sequence of
+// ncat = n_occ + m candidates: their K/V rows, the scores they already have
+// (zero for the chunk) and their positions are laid out contiguously per head.
+template <int ROWB>
+__global__ __launch_bounds__(256) void concat_kernel(
+    const char *__restrict__ Kc, const char *__restrict__ Vc, const float *__restrict__ acc_g,
+    const int32_t *__restrict__ pos_g, const char *__restrict__ Kn, const char *__restrict__ Vn,
+    int k, int n_occ, int m, int t, char *__restrict__ Kcat, char *__restrict__ Vcat,
+    float *__restrict__ base, int32_t *__restrict__ pos_cat)
+{
+    constexpr int LPR = ROWB / 16;
+    const int head = blockIdx.y, ncat = n_occ + m;
+    const int row = blockIdx.x * (256 / LPR) + threadIdx.x / LPR, li = threadIdx.x % LPR;
+    if (row >= ncat) return;
+    const bool cached = row < n_occ;
+    const char *ks = cached ? Kc + ((size_t)head * k + row) * ROWB : Kn + ((size_t)head * m + (row - n_occ)) * ROWB;
+    const char *vs = cached ? Vc + ((size_t)head * k + row) * ROWB : Vn + ((size_t)head * m + (row - n_occ)) * ROWB;
+    const size_t o = ((size_t)head * ncat + row) * ROWB + li * 16;
+    *reinterpret_cast<uint4 *>(Kcat + o) = *reinterpret_cast<const uint4 *>(ks + li * 16);
+    *reinterpret_cast<uint4 *>(Vcat + o) = *reinterpret_cast<const uint4 *>(vs + li * 16);
+    if (li == 0) {
+        base[(size_t)head * ncat + row] = cached ? acc_g[(size_t)head * k + row] : 0.f;
+        pos_cat[(size_t)head * ncat + row] = cached ? pos_g[(size_t)head * k + row] : t + (row - n_occ);
+    }
+}
+
+hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn, int m, int n_occ,
+                             void *Kcat, void *Vcat, float *base, int32_t *pos_cat, hipStream_t st)
+{
+    const int heads = c.cfg.batch * c.cfg.heads;
+    const int rowb = c.cfg.head_dim * c.esize;
+    const int ncat = n_occ + m;
+    if (heads > 65535) return hipErrorInvalidValue;
+#define H2O_CC(RB)                                                                               \
+    hipLaunchKernelGGL((concat_kernel<RB>), dim3((ncat + 256 / (RB / 16) - 1) / (256 / (RB / 16)), heads), \
+                       dim3(256), 0, st, c.K, c.V, c.acc, c.pos, static_cast<const char *>(Kn),  \
+                       static_cast<const char *>(Vn), c.k, n_occ, m, c.t, static_cast<char *>(Kcat), \
+                       static_cast<char *>(Vcat), base, pos_cat)
+    switch (rowb) {
+    case 128: H2O_CC(128); break;
+    case 256: H2O_CC(256); break;
+    case 512: H2O_CC(512); break;
+    default: return hipErrorInvalidValue;
+    }
+#undef H2O_CC
     return hipGetLastError();
 }

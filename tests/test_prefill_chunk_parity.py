@@ -1,0 +1,157 @@
+"""GPU parity of chunked prompt processing (h2o_prefill_chunk) against the CPU
+oracle, through the C ABI: accumulated scores and kept sets after every chunk."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.h2o_oracle import OracleHead, map_heads
+from tests import parity
+from tests.test_prefill_parity import COLSUM_ATOL, COLSUM_RTOL, SELECT_RTOL
+
+pytestmark = pytest.mark.gpu
+
+torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, decode_steps=0):
+    """Feeds the prompt chunk by chunk to the device and to the oracle.  After
+    every chunk: same kept positions (a difference is accepted only between tokens
+    whose oracle rank values lie within SELECT_RTOL of each other, i.e. at the
+    selection threshold; that head is then no longer compared), scores within the
+    column-sum tolerance.  Optionally continues with generation steps."""
+    from paper_2306_14048_amd import binding as hb, synth
+    dev = torch.device("cuda:0")
+    n = sum(chunks)
+    k = heavy + recent
+    Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, sigma, dev, seed)
+    cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, device=dev, rank=rank)
+    need = hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, max(chunks))
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    heads = [(b, h) for b in range(B) for h in range(Hh)]
+    scale = parity.oracle_scale(d)
+    oracles = {bh: OracleHead(d, heavy, recent, scale, score_f32=True, cap=n + decode_steps, policy=rank)
+               for bh in heads}
+    Qc, Kc, Vc = Q.cpu(), K.cpu(), V.cpu()
+    alive = set(heads)
+    flips = 0
+    t0 = 0
+    for m in chunks:
+        q, kk, v = (x[:, :, t0:t0 + m].contiguous() for x in (Q, K, V))
+        hb.h2o_prefill_chunk(cache.handle, q, kk, v, m, ws, need)
+        pos, acc = cache.snapshot()
+        torch.cuda.synchronize()
+        pos, acc = pos.cpu().numpy(), acc.cpu().numpy()
+        t1 = t0 + m
+        assert cache.tokens_seen == t1
+
+        def one(bh):
+            b, h = bh
+            oracles[bh].prefill_chunk(parity.host64(Qc[b, h, t0:t1]), parity.host64(Kc[b, h, t0:t1]),
+                                      parity.host64(Vc[b, h, t0:t1]))
+        map_heads(one, sorted(alive))
+        for (b, h) in sorted(alive):
+            o = oracles[(b, h)]
+            rp, rs = o.resident()
+            gp = pos[b, h][pos[b, h] >= 0]
+            assert len(gp) == len(rp) == min(t1, k)
+            assert np.all(np.diff(gp) > 0), "slots must hold ascending positions"
+            assert set(range(max(0, t1 - recent), t1)) <= set(gp.tolist()), "recent window not resident"
+            diff = set(gp.tolist()) ^ set(rp.tolist())
+            if diff:
+                # only tokens at the selection threshold may change sides
+                vals = [parity.rank_of(o, j, t1 - 1, rank) for j in diff]
+                thr = min(parity.rank_of(o, j, t1 - 1, rank) for j in rp.tolist() if j < t1 - recent)
+                assert all(abs(v - thr) <= SELECT_RTOL * max(abs(thr), 1e-30) for v in vals), \
+                    "tokens %s changed sides away from the threshold %.9g" % (sorted(diff), thr)
+                alive.discard((b, h))
+                flips += len(diff) // 2
+                continue
+            lut = dict(zip(rp.tolist(), rs.tolist()))
+            got = acc[b, h][:len(gp)].astype(np.float64)
+            ref = np.array([lut[int(j)] for j in gp])
+            assert np.all(np.abs(got - ref) <= COLSUM_RTOL * np.abs(ref) + COLSUM_ATOL), \
+                "scores differ after chunk ending at %d" % t1
+        t0 = t1
+    print("\n[chunked prompt] B=%d Hh=%d d=%d chunks=%s H=%d R=%d %s rank=%d: heads %d, dropped at threshold %d"
+          % (B, Hh, d, chunks if len(chunks) < 8 else "%dx%d" % (len(chunks), chunks[0]), heavy, recent,
+             str(dtype).split(".")[-1], rank, len(heads), len(heads) - len(alive)), flush=True)
+    assert len(alive) >= 0.9 * len(heads)
+    if decode_steps:
+        qs, ks, vs = synth.make_steps(B, Hh, d, decode_steps, dtype, sigma, dev, seed)
+        out = torch.empty((B, Hh, d), dtype=dtype, device=dev)
+        tol = parity.OUT_TOL[dtype] + parity.OUT_STORE_SLACK[dtype]
+        for s in range(decode_steps):
+            cache.decode_step(qs[s], ks[s], vs[s], out)
+            pos, _ = cache.snapshot()
+            torch.cuda.synchronize()
+            o_gpu, pos = out.cpu().double().numpy(), pos.cpu().numpy()
+            for (b, h) in sorted(alive):
+                o = oracles[(b, h)]
+                r = o.decode(parity.host64(qs[s, b, h]), parity.host64(ks[s, b, h]), parity.host64(vs[s, b, h]))
+                err = np.linalg.norm(o_gpu[b, h] - r.out) / max(np.linalg.norm(r.out), 1e-300)
+                assert err <= tol, "output after chunked prompt off by %.2e" % err
+                gp = set(pos[b, h][pos[b, h] >= 0].tolist())
+                if gp != set(o.resident()[0].tolist()):
+                    # scores carry the column-sum tolerance: a near-tie may break the other way
+                    assert np.isfinite(r.second) and (r.second - r.lowest) <= SELECT_RTOL * abs(r.second)
+                    alive.discard((b, h))
+        assert len(alive) >= 0.9 * len(heads)
+    cache.close()
+    return flips
+
+
+@pytest.mark.parametrize("dt,d", [("f16", 128), ("bf16", 128), ("f32", 64), ("f16", 64)])
+@pytest.mark.parametrize("chunks,heavy,recent", [
+    ([300, 300, 300], 64, 64),          # chunk > budget
+    ([40] * 12, 100, 60),               # chunk < recent window: cached tokens stay in the window
+    ([1, 255, 256, 257, 31], 50, 50),   # ragged chunk sizes, a chunk of one
+    ([700], 64, 64),                    # one chunk = the one-shot prompt phase
+    ([100, 50], 200, 200),              # nothing evicted
+])
+def test_chunked_prompt(dt, d, chunks, heavy, recent):
+    chunk_case(2, 2, d, chunks, heavy, recent, torch_dt[dt], 1.0, 51)
+
+
+def test_chunked_prompt_heavy_only_and_window_only():
+    chunk_case(1, 3, 128, [200, 200, 200], 80, 0, torch.float16, 1.0, 52)
+    chunk_case(1, 3, 128, [200, 200, 200], 0, 80, torch.float16, 1.0, 53)
+
+
+def test_chunked_prompt_averaged_ranking():
+    chunk_case(2, 2, 128, [256, 256, 256, 100], 64, 64, torch.float16, 1.0, 54, rank=1)
+
+
+def test_chunked_prompt_then_generation():
+    chunk_case(2, 2, 128, [512, 512, 300], 103, 102, torch.float16, 1.0, 55, decode_steps=12)
+
+
+def test_chunked_prompt_large_budget_and_chunks():
+    """OPT-6.7B-shaped budget (205 + 205) fed in 1024-token chunks, and a
+    2048 + 2048 budget fed in 2048-token chunks."""
+    chunk_case(1, 4, 128, [1024] * 4, 205, 205, torch.float16, 1.0, 56)
+    chunk_case(1, 2, 128, [2048] * 3, 2048, 2048, torch.bfloat16, 1.0, 57)
+
+
+def test_chunk_refused_after_an_eviction_and_allowed_after_reset():
+    from paper_2306_14048_amd import binding as hb, synth
+    dev = torch.device("cuda:0")
+    B, Hh, d, dtype = 1, 2, 64, torch.float16
+    Q, K, V = synth.make_prompt(B, Hh, 64, d, dtype, 1.0, dev, 3)
+    cache = hb.H2OCache(B, Hh, d, 8, 8, dtype, device=dev)
+    need = hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, 64)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, need)
+    qs, ks, vs = synth.make_steps(B, Hh, d, 1, dtype, 1.0, dev, 3)
+    out = torch.empty((B, Hh, d), dtype=dtype, device=dev)
+    cache.decode_step(qs[0], ks[0], vs[0], out)            # evicts: slots are no longer in position order
+    with pytest.raises(hb.H2OError) as ei:
+        hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, need)
+    assert ei.value.status == hb.H2O_ESTATE
+    cache.reset()
+    hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, need)
+    assert cache.tokens_seen == 64
+    with pytest.raises(hb.H2OError) as ei:
+        hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, 16)
+    assert ei.value.status == hb.H2O_ENOMEM
+    cache.close()
