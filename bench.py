@@ -130,10 +130,13 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = all)")
-    ap.add_argument("--prompt", choices=("scores", "attention"), default="scores",
+    ap.add_argument("--prompt", choices=("scores", "attention", "chunked"), default="scores",
                     help="prompt phase: 'scores' = row statistics + column sums + compression (the "
                          "default step); 'attention' = causal attention output whose row statistics "
-                         "feed the column sums, + compression (a layer's whole prompt phase)")
+                         "feed the column sums, + compression (a layer's whole prompt phase); "
+                         "'chunked' = the prompt in chunks of --chunk tokens, each scored against "
+                         "cache + chunk and compressed to the budget (bounded memory)")
+    ap.add_argument("--chunk", type=int, default=1024, help="chunk length for --prompt chunked")
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="profiling aid: run only this many generation steps per pass (0 = the "
                          "workload's own count); the JSON line reports the count it ran")
@@ -169,6 +172,13 @@ def main():
             ws = torch.empty(hb.h2o_prefill_attention_workspace_bytes(cache.cfg, n),
                              dtype=torch.uint8, device=dev)
             attn_out = torch.empty_like(Q)
+        chunks = []
+        if args.prompt == "chunked":
+            # the chunk entry point takes [B, Hh, m, d] blocks: cut the prompt up before the clock starts
+            m = max(1, min(args.chunk, n))
+            ws = torch.empty(hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, m), dtype=torch.uint8, device=dev)
+            for t0 in range(0, n, m):
+                chunks.append(tuple(x[:, :, t0:t0 + m].contiguous() for x in (Q, K, V)))
         Qp, Kp, Vp, wsp, wsn = Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel()
         caches.append(cache)
     else:
@@ -207,6 +217,10 @@ def main():
         if L == 1 and args.prompt == "attention":
             hb.h2o_prefill_attention_scores(ptrs[0][0], Qp, Kp, Vp, n, wsp, wsn, attn_out.data_ptr(),
                                             None, sp)
+        elif L == 1 and args.prompt == "chunked":
+            for (cq, ck, cv) in chunks:
+                hb.h2o_prefill_chunk(ptrs[0][0], cq.data_ptr(), ck.data_ptr(), cv.data_ptr(),
+                                     cq.shape[2], wsp, wsn, sp)
         elif L == 1:
             hb.h2o_prefill_scores(ptrs[0][0], Qp, Kp, Vp, n, wsp, wsn, None, sp)
         if timed_events:
@@ -252,7 +266,7 @@ def main():
 
         # the two matrix-core passes of the prompt phase on their own
         pre_pass_ms = attn_ms = None
-        if L == 1:
+        if L == 1 and args.prompt != "chunked":
             pre_pass_ms = time_prefill_passes(hb, caches[0].cfg, Q, K, n, ws, stream)
         if L == 1 and args.prompt == "attention":
             attn_ms = time_attention(hb, caches[0].cfg, Q, K, V, n, ws, attn_out, stream)
@@ -315,6 +329,24 @@ def main():
                                      "kernel": "transpose_v_kernel + prefill_attn_kernel",
                                      "flops_per_launch": fl, "ms_per_launch": attn_ms}
         rec["config"]["prompt_phase"] = "attention output + column sums + compression"
+    if L == 1 and args.prompt == "chunked":
+        # logits the two passes form over all chunks: every chunk query against the
+        # cached tokens and the chunk's own visible part
+        pairs, occ = 0, 0
+        for (cq, _, _) in chunks:
+            m = cq.shape[2]
+            pairs += m * occ + m * (m + 1) // 2
+            occ = min(k, occ + m)
+        fl = 2 * 2 * d * pairs * B * Hh
+        tf = fl / (min(prefill_ms) * 1e-3) / 1e12
+        mfma_roofline = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf / MFMA_PEAK_TFLOPS, "traffic": None,
+                         "kernel": "whole chunked prompt phase: per chunk concat_kernel + two "
+                                   "prefill_pass_kernel launches + select_gather_kernel",
+                         "flops": fl, "ms": min(prefill_ms), "chunk": chunks[0][0].shape[2],
+                         "chunks": len(chunks)}
+        rec["config"]["prompt_phase"] = "chunks of %d tokens, compressed to the budget after each" \
+            % chunks[0][0].shape[2]
     if T > 0:
         # the dominant kernel: the generation step, HBM-bound
         rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -86,6 +86,8 @@ def _ptr(x):
         return None
     if isinstance(x, int):
         return x
+    if not x.is_contiguous():
+        raise ValueError("the C ABI takes dense row-major arrays; got a non-contiguous tensor")
     return x.data_ptr()
 
 
@@ -256,6 +258,16 @@ class H2OCache:
         n = Q.shape[-2]
         ws = self.workspace(n)
         h2o_prefill_scores(self.handle, Q, K, V, n, ws, ws.numel(), colsum_out, stream)
+
+    def prefill_chunk(self, Q, K, V, stream=None):
+        """The next Q.shape[-2] prompt tokens as one chunk ([batch, heads, m, head_dim], contiguous)."""
+        m = Q.shape[-2]
+        need = h2o_prefill_chunk_workspace_bytes(self.cfg, m)
+        if need == 0:
+            raise H2OError(H2O_EUNSUPPORTED, "h2o_prefill_chunk_workspace_bytes")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        h2o_prefill_chunk(self.handle, Q, K, V, m, self._ws, self._ws.numel(), stream)
 
     def prefill_select(self, K, V, score, stream=None):
         h2o_prefill_select(self.handle, K, V, score, K.shape[-2], stream)
