@@ -60,6 +60,24 @@
  *     chunk is compressed by the prompt rule.  m = 1 is the generation step,
  *     one chunk holding the whole prompt is the one-shot prompt phase.
  *
+ *   - `kv_bits` 4 (h2o_oracle_set_kv_bits): cached keys and values are STORED
+ *     as group-wise 4-bit codes (Sec. 5.4 "compatible with quantization",
+ *     App. "Throughput improvement ... combining with quantization": the
+ *     group-wise min-max quantisation of the serving system the paper builds
+ *     on; the paper gives no formula, this is the published one).  Along the
+ *     head dimension, per group of g consecutive elements:
+ *         mn = min, mx = max, scale = (mx - mn) / 15,
+ *         code_i = clamp(round_half_even((x_i - mn) / scale), 0, 15),
+ *         stored value = mn + code_i * scale      (scale = 0: code 0, value mn).
+ *     The code decision is an integer decided by floating point, so its
+ *     precision is fixed: every operation above is one binary32 operation on
+ *     binary32 inputs (cache element types convert exactly).  A row is
+ *     quantised when it ENTERS the cache: the kept rows after a prompt phase,
+ *     and the new token after its own generation step, in which it still
+ *     attends to itself with its unquantised key and value.  Scores and
+ *     eviction are untouched.  Chunked prompt processing is not defined with
+ *     quantised storage here (returns -1).
+ *
  * Pins (tests/test_oracle_pins.py): brute-force set-function evaluation on tiny
  * inputs, reduction to textbook causal softmax attention when the budget
  * covers the sequence, harmonic-number closed form for equal logits, sliding
@@ -89,6 +107,11 @@ typedef struct h2o_oracle {
     double queries;          /* number of softmax rows accumulated so far */
     double *s;          /* [cap] scratch: logits */
     double *p;          /* [cap] scratch: probabilities */
+    int kv_bits;        /* 0: rows stored as given; 4: group-wise 4-bit codes */
+    int group;          /* elements per quantisation group */
+    unsigned char *quantised; /* [cap] row has been replaced by its stored value */
+    unsigned char *Kcode, *Vcode;   /* [cap][d] codes 0..15 */
+    float *Kpar, *Vpar;             /* [cap][d/group][2] (scale, min) */
 } h2o_oracle;
 
 h2o_oracle *h2o_oracle_new(int d, int heavy, int recent, double scale,
@@ -118,7 +141,76 @@ void h2o_oracle_free(h2o_oracle *o)
 {
     if (!o) return;
     free(o->K); free(o->V); free(o->acc); free(o->resident);
-    free(o->s); free(o->p); free(o);
+    free(o->s); free(o->p);
+    free(o->quantised); free(o->Kcode); free(o->Vcode); free(o->Kpar); free(o->Vpar);
+    free(o);
+}
+
+/* Store cached rows as 4-bit codes in groups of `group` elements (bits = 4), or
+ * as given (bits = 0).  Only on an object that has seen no token. */
+int h2o_oracle_set_kv_bits(h2o_oracle *o, int bits, int group)
+{
+    if (!o || o->t != 0 || (bits != 0 && bits != 4)) return -1;
+    if (bits == 4 && (group < 1 || o->d % group != 0)) return -1;
+    o->kv_bits = bits;
+    if (bits == 0) return 0;
+    o->group = group;
+    const size_t cap = (size_t)o->cap, ng = (size_t)(o->d / group);
+    if (!o->quantised) {
+        o->quantised = (unsigned char *)calloc(cap, 1);
+        o->Kcode = (unsigned char *)calloc(cap * o->d, 1);
+        o->Vcode = (unsigned char *)calloc(cap * o->d, 1);
+        o->Kpar = (float *)calloc(cap * ng * 2, sizeof(float));
+        o->Vpar = (float *)calloc(cap * ng * 2, sizeof(float));
+    }
+    return (o->quantised && o->Kcode && o->Vcode && o->Kpar && o->Vpar) ? 0 : -1;
+}
+
+/* One group of g elements: codes, (scale, min), and the stored values written
+ * back over x.  Every step is a single binary32 operation (the volatiles keep
+ * the compiler from contracting or widening them). */
+static void quantise_group(double *x, int g, unsigned char *code, float *par)
+{
+    volatile float mn = (float)x[0], mx = (float)x[0];
+    for (int i = 1; i < g; ++i) {
+        const float v = (float)x[i];
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    volatile float range = mx - mn;
+    volatile float scale = range / 15.0f;
+    par[0] = scale; par[1] = mn;
+    for (int i = 0; i < g; ++i) {
+        float c = 0.0f;
+        if (scale > 0.0f) {
+            volatile float dist = (float)x[i] - mn;
+            volatile float steps = dist / scale;
+            c = rintf(steps);                 /* default rounding mode: half to even */
+            if (c < 0.0f) c = 0.0f;
+            if (c > 15.0f) c = 15.0f;
+        }
+        code[i] = (unsigned char)c;
+        x[i] = (double)mn + (double)c * (double)scale;
+    }
+}
+
+/* Replace the key and value rows of `pos` by what the quantised cache holds. */
+static void store_row(h2o_oracle *o, int pos)
+{
+    if (o->kv_bits != 4 || o->quantised[pos]) return;
+    const int d = o->d, g = o->group, ng = d / g;
+    for (int b = 0; b < ng; ++b) {
+        const size_t e = (size_t)pos * d + (size_t)b * g, q = ((size_t)pos * ng + b) * 2;
+        quantise_group(o->K + e, g, o->Kcode + e, o->Kpar + q);
+        quantise_group(o->V + e, g, o->Vcode + e, o->Vpar + q);
+    }
+    o->quantised[pos] = 1;
+}
+
+static void store_resident_rows(h2o_oracle *o, int first, int end)
+{
+    for (int j = first; j < end; ++j)
+        if (o->resident[j]) store_row(o, j);
 }
 
 /* Add one probability to a stored score, in the storage precision. */
@@ -245,6 +337,7 @@ int h2o_oracle_prefill(h2o_oracle *o, const double *Q, const double *K,
         for (int j = 0; j < n; ++j) o->acc[j] = (double)(float)o->acc[j];
 
     compress_prompt(o, n);
+    store_resident_rows(o, 0, n);
     return 0;
 }
 
@@ -266,7 +359,7 @@ int h2o_oracle_prefill_chunk(h2o_oracle *o, const double *Q, const double *K,
                              const double *V, int m, double *colsum_out,
                              double *attn_out)
 {
-    if (!o || !Q || !K || !V || m <= 0 || o->t + m > o->cap) return -1;
+    if (!o || !Q || !K || !V || m <= 0 || o->t + m > o->cap || o->kv_bits != 0) return -1;
     const int d = o->d, t0 = o->t, t1 = o->t + m;
     memcpy(o->K + (size_t)t0 * d, K, (size_t)m * d * sizeof(double));
     memcpy(o->V + (size_t)t0 * d, V, (size_t)m * d * sizeof(double));
@@ -347,6 +440,7 @@ int h2o_oracle_load_and_select(h2o_oracle *o, const double *K, const double *V,
     }
     o->queries = (double)n;
     compress_prompt(o, n);
+    store_resident_rows(o, 0, n);
     return 0;
 }
 
@@ -417,6 +511,7 @@ int h2o_oracle_decode(h2o_oracle *o, const double *q, const double *k_new,
     if (info) { info[0] = evicted; info[1] = n_cand; }
     if (low) { low[0] = lowest; low[1] = second; }
     o->t = t + 1;
+    if (o->resident[t]) store_row(o, t);    /* the token enters the cache now */
     return 0;
 }
 
@@ -429,6 +524,7 @@ int h2o_oracle_resync(h2o_oracle *o, int restore_pos, int evict_pos)
     if (o->resident[restore_pos] || !o->resident[evict_pos]) return -1;
     o->resident[restore_pos] = 1; o->evicted_mass -= o->acc[restore_pos];
     o->resident[evict_pos] = 0;   o->evicted_mass += o->acc[evict_pos];
+    store_row(o, restore_pos);
     return 0;
 }
 
@@ -454,6 +550,20 @@ int h2o_oracle_resident(const h2o_oracle *o, int *pos_out, double *score_out)
         ++c;
     }
     return c;
+}
+
+/* The 4-bit codes ([d] each, one per byte) and the (scale, min) pairs
+ * ([d/group][2] each) a quantised cache holds for resident position `pos`. */
+int h2o_oracle_token_codes(const h2o_oracle *o, int pos, unsigned char *kcode,
+                           float *kpar, unsigned char *vcode, float *vpar)
+{
+    if (!o || o->kv_bits != 4 || pos < 0 || pos >= o->t || !o->quantised[pos]) return -1;
+    const size_t d = (size_t)o->d, np = (size_t)(o->d / o->group) * 2;
+    if (kcode) memcpy(kcode, o->Kcode + pos * d, d);
+    if (vcode) memcpy(vcode, o->Vcode + pos * d, d);
+    if (kpar) memcpy(kpar, o->Kpar + pos * np, np * sizeof(float));
+    if (vpar) memcpy(vpar, o->Vpar + pos * np, np * sizeof(float));
+    return 0;
 }
 
 /* Key/value history row (what a cache slot holding `pos` must contain). */

@@ -66,6 +66,10 @@ def _load():
     lib.h2o_oracle_score.restype = ctypes.c_double
     lib.h2o_oracle_resident.argtypes = [P, I, D]
     lib.h2o_oracle_token_kv.argtypes = [P, ctypes.c_int, D, D]
+    U8 = ctypes.POINTER(ctypes.c_ubyte)
+    F = ctypes.POINTER(ctypes.c_float)
+    lib.h2o_oracle_set_kv_bits.argtypes = [P, ctypes.c_int, ctypes.c_int]
+    lib.h2o_oracle_token_codes.argtypes = [P, ctypes.c_int, U8, F, U8, F]
     _lib = lib
     return lib
 
@@ -97,7 +101,8 @@ class OracleHead:
     """One (batch, head) pair of the H2O process, position-indexed."""
 
     def __init__(self, d: int, heavy: int, recent: int, scale: float | None = None,
-                 score_f32: bool = False, cap: int = 4096, policy: int = 0):
+                 score_f32: bool = False, cap: int = 4096, policy: int = 0, kv_bits: int = 0,
+                 group: int = 64):
         self._lib = _load()
         self.d, self.heavy, self.recent = int(d), int(heavy), int(recent)
         self.budget = self.heavy + self.recent
@@ -109,6 +114,9 @@ class OracleHead:
             raise ValueError("bad oracle configuration")
         if self._lib.h2o_oracle_set_policy(self._h, int(policy)) != 0:
             raise ValueError("unknown eviction policy %r" % (policy,))
+        self.kv_bits, self.group = int(kv_bits), int(group)
+        if self._lib.h2o_oracle_set_kv_bits(self._h, self.kv_bits, self.group) != 0:
+            raise ValueError("unsupported cache storage: %r bits in groups of %r" % (kv_bits, group))
 
     def __del__(self):
         h = getattr(self, "_h", None)
@@ -202,6 +210,19 @@ class OracleHead:
             self._h, pos.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), _dp(sc))
         assert got == c
         return pos[:c], sc[:c]
+
+    def token_codes(self, pos: int):
+        """What a 4-bit cache holds for resident position `pos`: key codes uint8[d],
+        key (scale, min) float32[d/group, 2], value codes, value (scale, min)."""
+        ng = self.d // self.group
+        kc, vc = np.empty(self.d, np.uint8), np.empty(self.d, np.uint8)
+        kp, vp = np.empty((ng, 2), np.float32), np.empty((ng, 2), np.float32)
+        u8, f = ctypes.POINTER(ctypes.c_ubyte), ctypes.POINTER(ctypes.c_float)
+        rc = self._lib.h2o_oracle_token_codes(self._h, int(pos), kc.ctypes.data_as(u8), kp.ctypes.data_as(f),
+                                              vc.ctypes.data_as(u8), vp.ctypes.data_as(f))
+        if rc != 0:
+            raise RuntimeError("no stored codes for position %d" % pos)
+        return kc, kp, vc, vp
 
     def token_kv(self, pos: int):
         k = np.empty(self.d, dtype=np.float64)

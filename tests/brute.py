@@ -27,14 +27,40 @@ def _rank(acc, members, last_q, policy, score_dtype):
     return {s: acc[s] / (last_q - s + 1) for s in members}
 
 
-def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0):
+def nearest_level_quantise(row, group):
+    """Group-wise 4-bit storage of one row, by search: per group of `group`
+    elements the 16 levels are evenly spaced from the group's minimum to its
+    maximum (spacing and minimum held in binary32) and every element is replaced
+    by the level closest to it.  Returns (stored row float64, codes, every
+    element's distance to the nearest half-way point in units of the spacing)."""
+    row = np.asarray(row, np.float64)
+    out, codes = np.empty_like(row), np.empty(row.shape, np.int64)
+    margin = np.full(row.shape, np.inf)
+    for g0 in range(0, row.size, group):
+        x = row[g0:g0 + group]
+        mn, mx = np.float32(x.min()), np.float32(x.max())
+        step = np.float32(np.float32(mx - mn) / np.float32(15))
+        levels = np.float64(mn) + np.arange(16) * np.float64(step)
+        dist = np.abs(x[:, None] - levels[None, :])
+        c = dist.argmin(axis=1)
+        if step > 0:
+            frac = (x - np.float64(mn)) / np.float64(step)
+            margin[g0:g0 + group] = np.where(frac < 15, np.abs(frac - np.floor(frac) - 0.5), np.inf)
+        codes[g0:g0 + group] = c
+        out[g0:g0 + group] = levels[c]
+    return out, codes, margin
+
+
+def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0, store=None):
     """Q, K, V: [N, d] for all N = n + T tokens.  Returns a dict with
     per-decode-step outputs, resident sets after every call, evicted tokens,
-    prompt column sums and final scores."""
-    Q = np.asarray(Q, np.float64); K = np.asarray(K, np.float64); V = np.asarray(V, np.float64)
+    prompt column sums and final scores.  `store` (row -> row) is what the cache
+    does to a key or value row when the token enters it (after the prompt phase,
+    or after the token's own step); the token's own step sees the row as given."""
+    Q = np.asarray(Q, np.float64); K = np.asarray(K, np.float64).copy(); V = np.asarray(V, np.float64).copy()
     N, d = Q.shape
     k = heavy + recent
-    S = scale * (Q @ K.T)                       # every logit there is
+    S = scale * (Q @ K.T)                       # every logit there is (rows are redone if rows change)
 
     acc = np.zeros(N)
     member = np.zeros(N, dtype=bool)
@@ -65,10 +91,15 @@ def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0
             older.sort(key=lambda j: (r[j], j), reverse=True)
             member[older[:heavy]] = True
         sets.append(set(np.flatnonzero(member).tolist()))
+        if store is not None:
+            for j in np.flatnonzero(member):
+                K[j], V[j] = store(K[j]), store(V[j])
 
     for t in range(n, N):
         G = member.copy()
         G[t] = True
+        if store is not None:
+            S[t] = scale * (K @ Q[t])             # against the rows as the cache holds them now
         row = np.where(G, S[t], -np.inf)
         e = np.exp(row - row.max())
         p = e / e.sum()                           # zero outside G
@@ -90,6 +121,8 @@ def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0
             G[u] = False
         evicted.append(u)
         member = G
+        if store is not None and member[t]:
+            K[t], V[t] = store(K[t]), store(V[t])
         sets.append(set(np.flatnonzero(member).tolist()))
     return dict(outs=np.array(outs), sets=sets, evicted=evicted, colsum=colsum,
                 attn_prompt=attn_prompt, acc=acc)

@@ -511,3 +511,180 @@ def test_chunking_is_invisible_while_nothing_is_evicted():
         pos, sc = o.resident()
         assert pos.tolist() == list(range(n))
         np.testing.assert_allclose(sc, col, rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------ 4-bit group-wise cache storage
+from tests.brute import nearest_level_quantise  # noqa: E402
+
+
+def as_stored(x, kind):
+    """Random rows as a cache element type would hold them (exactly representable)."""
+    t = torch.from_numpy(np.asarray(x, np.float64))
+    dt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[kind]
+    return t.to(dt).double().numpy()
+
+
+def dequantise(codes, par, group):
+    """Stored values from codes and (scale, min) pairs, in exact arithmetic (fp64 holds
+    a 4-bit integer times a binary32 plus a binary32 to well below 1e-15 relative)."""
+    c = codes.astype(np.float64).reshape(-1, group)
+    return (par[:, 1:2].astype(np.float64) + c * par[:, 0:1].astype(np.float64)).reshape(-1)
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("d,group", [(128, 64), (64, 64), (8, 4)])
+def test_quantised_rows_are_the_nearest_of_sixteen_even_levels(kind, d, group):
+    rng = np.random.default_rng(7)
+    n = 24
+    K = as_stored(rng.standard_normal((n, d)) * np.exp(rng.standard_normal((n, 1))), kind)
+    V = as_stored(rng.standard_normal((n, d)), kind)
+    o = OracleHead(d, n, n, 0.3, cap=n, kv_bits=4, group=group)
+    o.prefill(as_stored(rng.standard_normal((n, d)), kind), K, V)     # budget covers it: all kept
+    seen = unclear = 0
+    for j in range(n):
+        kc, kp, vc, vp = o.token_codes(j)
+        for row, codes, par in ((K[j], kc, kp), (V[j], vc, vp)):
+            ref, ref_codes, margin = nearest_level_quantise(row, group)
+            # an element on a half-way point (16-bit data hit them exactly now and then) may
+            # go either way in the search; everywhere else the code is the nearest level
+            clear = margin > 1e-6
+            seen += clear.size; unclear += int((~clear).sum())
+            np.testing.assert_array_equal(codes[clear], ref_codes[clear])
+            assert np.all(np.abs(codes.astype(np.int64) - ref_codes) <= 1)
+            g = row.reshape(-1, group)
+            np.testing.assert_array_equal(par[:, 1], g.min(axis=1).astype(np.float32))
+            np.testing.assert_array_equal(
+                par[:, 0], ((g.max(axis=1).astype(np.float32) - g.min(axis=1).astype(np.float32))
+                            / np.float32(15)).astype(np.float32))
+            stored = dequantise(codes, par, group)
+            np.testing.assert_allclose(stored[clear], ref[clear], rtol=0, atol=1e-12)
+            # uniform quantiser: never further than half a step from the input; ends are exact
+            step = np.repeat(par[:, 0].astype(np.float64), group)
+            assert np.all(np.abs(stored - row) <= 0.5 * step * (1 + 1e-6))
+            cg = codes.reshape(-1, group)
+            assert np.all(cg.min(axis=1) == 0) and np.all(cg.max(axis=1) == 15)
+            assert np.all(cg[np.arange(len(g)), g.argmin(axis=1)] == 0)
+            assert np.all(cg[np.arange(len(g)), g.argmax(axis=1)] == 15)
+        ks, vs = o.token_kv(j)
+        np.testing.assert_array_equal(ks, dequantise(kc, kp, group))
+        np.testing.assert_array_equal(vs, dequantise(vc, vp, group))
+    assert unclear < 0.03 * seen
+
+
+def test_quantised_constant_group_and_group_independence():
+    d, group = 8, 4
+    K = np.array([[2.5] * 4 + [1.0, -3.0, 0.25, 7.0]])
+    V = np.array([[0.0] * 4 + [0.5, 0.5, 0.5, 0.5]])
+    o = OracleHead(d, 1, 1, 1.0, cap=4, kv_bits=4, group=group)
+    o.prefill(np.ones((1, d)), K, V)
+    kc, kp, vc, vp = o.token_codes(0)
+    assert kp[0, 0] == 0 and kp[0, 1] == 2.5 and np.all(kc[:4] == 0)
+    assert np.all(vc == 0) and np.all(vp[:, 0] == 0) and list(vp[:, 1]) == [0.0, 0.5]
+    np.testing.assert_array_equal(o.token_kv(0)[1], V[0])
+    # the second group's contents do not reach the first group's codes
+    K2 = K.copy(); K2[0, :4] = [1.0, 2.0, 4.0, 1.5]
+    K3 = K2.copy(); K3[0, 4:] = [100.0, -100.0, 3.0, 0.0]
+    a = OracleHead(d, 1, 1, 1.0, cap=4, kv_bits=4, group=group); a.prefill(np.ones((1, d)), K2, V)
+    b = OracleHead(d, 1, 1, 1.0, cap=4, kv_bits=4, group=group); b.prefill(np.ones((1, d)), K3, V)
+    np.testing.assert_array_equal(a.token_codes(0)[0][:4], b.token_codes(0)[0][:4])
+    np.testing.assert_array_equal(a.token_codes(0)[1][0], b.token_codes(0)[1][0])
+    assert list(a.token_codes(0)[0][:4]) == [0, 5, 15, 2]      # (x - 1) / 0.2 = 0, 5, 15, 2.5 -> even
+
+
+def grid_rows(rng, n, d, group):
+    """Rows that lie exactly on their own 16 levels (spacing a power of two, both
+    ends present in every group): storing them in 4 bits loses nothing."""
+    rows = np.empty((n, d))
+    for i in range(n):
+        for g0 in range(0, d, group):
+            c = rng.integers(0, 16, group)
+            c[rng.permutation(group)[:2]] = [0, 15]
+            rows[i, g0:g0 + group] = rng.integers(-16, 16) / 8.0 + c * 2.0 ** rng.integers(-4, 1)
+    return rows
+
+
+@pytest.mark.parametrize("f32", [False, True])
+@pytest.mark.parametrize("n,T,heavy,recent", [(20, 30, 4, 4), (0, 40, 3, 5), (16, 24, 6, 0)])
+def test_rows_on_their_levels_make_quantised_storage_invisible(n, T, heavy, recent, f32):
+    rng = np.random.default_rng(n + T)
+    d, group = 16, 8
+    Q = rng.standard_normal((n + T, d))
+    K, V = grid_rows(rng, n + T, d, group), grid_rows(rng, n + T, d, group)
+    runs = []
+    for bits in (0, 4):
+        o = OracleHead(d, heavy, recent, 0.25, score_f32=f32, cap=n + T, kv_bits=bits, group=group)
+        outs, ev = [], []
+        if n:
+            o.prefill(Q[:n], K[:n], V[:n])
+        for t in range(n, n + T):
+            r = o.decode(Q[t], K[t], V[t])
+            outs.append(r.out); ev.append(r.evicted)
+        runs.append((np.array(outs), ev, o.resident()))
+    np.testing.assert_array_equal(runs[0][0], runs[1][0])
+    assert runs[0][1] == runs[1][1]
+    np.testing.assert_array_equal(runs[0][2][0], runs[1][2][0])
+    np.testing.assert_array_equal(runs[0][2][1], runs[1][2][1])
+
+
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("n,T,heavy,recent", [(8, 12, 2, 2), (0, 16, 2, 3), (12, 8, 4, 0), (9, 9, 0, 3)])
+def test_quantised_cache_matches_brute_force(seed, n, T, heavy, recent):
+    d, group = 8, 4
+    # binary32 data: 16-bit data land on half-way points between levels too often for a search
+    Q, K, V = (as_stored(x, "f32") for x in make_inputs(3000 + seed, n + T, d))
+    scale = 0.5
+    margins = []
+
+    def store(row):
+        out, _, margin = nearest_level_quantise(row, group)
+        margins.append(margin.min())
+        return out
+    ref = brute_h2o(Q, K, V, n, heavy, recent, scale, store=store)
+    assert min(margins) > 1e-4, "test data sits on a half-way point; pick another seed"
+    o = OracleHead(d, heavy, recent, scale, cap=n + T, kv_bits=4, group=group)
+    sets, outs, ev = [], [], []
+    if n:
+        o.prefill(Q[:n], K[:n], V[:n])
+        sets.append(set(o.resident()[0].tolist()))
+    for t in range(n, n + T):
+        r = o.decode(Q[t], K[t], V[t])
+        if np.isfinite(r.second):
+            assert r.second - r.lowest > 1e-9
+        outs.append(r.out); ev.append(r.evicted); sets.append(set(o.resident()[0].tolist()))
+    assert sets == ref["sets"] and ev == ref["evicted"]
+    np.testing.assert_allclose(np.array(outs), ref["outs"], rtol=1e-12, atol=1e-13)
+    pos, sc = o.resident()
+    np.testing.assert_allclose(sc, ref["acc"][pos], rtol=1e-12, atol=1e-14)
+    # the run differs from unquantised storage (the pin above is not vacuous)
+    plain = brute_h2o(Q, K, V, n, heavy, recent, scale)
+    assert np.abs(plain["outs"] - ref["outs"]).max() > 1e-4
+
+
+def test_token_attends_to_itself_unquantised_and_is_stored_quantised():
+    d, group = 8, 4
+    rng = np.random.default_rng(5)
+    q, k, v = (as_stored(rng.standard_normal((2, d)), "f16") for _ in range(3))
+    o = OracleHead(d, 2, 2, 0.5, cap=4, kv_bits=4, group=group)
+    r0 = o.decode(q[0], k[0], v[0])
+    np.testing.assert_array_equal(r0.out, v[0])          # alone in the cache: p_self = 1, its own value as given
+    kc, kp, vc, vp = o.token_codes(0)
+    k0, v0 = dequantise(kc, kp, group), dequantise(vc, vp, group)
+    assert np.abs(k0 - k[0]).max() > 1e-3 and np.abs(v0 - v[0]).max() > 1e-3
+    r1 = o.decode(q[1], k[1], v[1])
+    s = 0.5 * np.array([q[1] @ k0, q[1] @ k[1]])         # stored key for token 0, own key as given
+    p = np.exp(s - s.max()); p /= p.sum()
+    np.testing.assert_allclose(r1.out, p[0] * v0 + p[1] * v[1], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(o.score(0), 1.0 + p[0], rtol=1e-14)
+
+
+def test_quantised_storage_arguments():
+    with pytest.raises(ValueError):
+        OracleHead(8, 2, 2, kv_bits=8)
+    with pytest.raises(ValueError):
+        OracleHead(8, 2, 2, kv_bits=4, group=3)
+    o = OracleHead(8, 2, 2, cap=16, kv_bits=4, group=4)
+    x = np.zeros((3, 8))
+    with pytest.raises(RuntimeError):
+        o.prefill_chunk(x, x, x)                          # not defined with quantised storage
+    with pytest.raises(RuntimeError):
+        OracleHead(8, 2, 2, cap=16).token_codes(0)
