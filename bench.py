@@ -37,11 +37,15 @@ PROFILED_PREFILL_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 1191.2e6, "prefill_bf16":
                                   "opt30b_layer_f16": 4227.1e6}
 
 
-def decode_bytes_per_head_step(k: int, d: int, esize: int) -> int:
+def decode_bytes_per_head_step(k: int, d: int, esize: int, kv_bits: int = 0) -> int:
     """Algorithmic bytes one head moves per generation step: K and V rows read
     once, scores read + written and positions read (12 B per slot), q / k_new /
     v_new read and the new K row, V row and output written (6 rows), plus the
-    victim's score and position written (8 B)."""
+    victim's score and position written (8 B).  With 4-bit storage a cached row is
+    d/2 bytes of codes + 8 bytes of (scale, min) per 64 elements."""
+    if kv_bits == 4:
+        row = d // 2 + 8 * (d // 64)
+        return 2 * k * row + 12 * k + 4 * d * esize + 2 * row + 8
     return 2 * k * d * esize + 12 * k + 6 * d * esize + 8
 
 
@@ -137,6 +141,8 @@ def main():
                          "'chunked' = the prompt in chunks of --chunk tokens, each scored against "
                          "cache + chunk and compressed to the budget (bounded memory)")
     ap.add_argument("--chunk", type=int, default=1024, help="chunk length for --prompt chunked")
+    ap.add_argument("--kv-bits", type=int, default=0, choices=(0, 4),
+                    help="cache storage: 0 = the workload's element type, 4 = 4-bit group-wise codes")
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="profiling aid: run only this many generation steps per pass (0 = the "
                          "workload's own count); the JSON line reports the count it ran")
@@ -165,7 +171,7 @@ def main():
     caches, steps_in = [], []
     if L == 1:
         Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev)
-        cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
+        cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev, kv_bits=args.kv_bits)
         ws = cache.workspace(n)
         attn_out = None
         if args.prompt == "attention":
@@ -188,7 +194,7 @@ def main():
         # generation phase: T token steps, each visiting every layer in turn
         for layer in range(L):
             Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev, layer=layer)
-            cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev)
+            cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev, kv_bits=args.kv_bits)
             cache.prefill_scores(Q, K, V)
             torch.cuda.synchronize()
             cache._ws = None
@@ -302,7 +308,7 @@ def main():
     if T > 0:
         dec_us_eager = min(decode_ms) * 1e3 / (T * L)
         dec_us = dec_graph_us if dec_graph_us is not None else dec_us_eager
-        bytes_per_launch = decode_bytes_per_head_step(k, d, esize) * B * Hh
+        bytes_per_launch = decode_bytes_per_head_step(k, d, esize, args.kv_bits) * B * Hh
         achieved = bytes_per_launch / (dec_us * 1e-6) / 1e9
     rec = {
         "metric": "H2O decode step: achieved HBM GB/s (% peak) + tokens/s, OPT-6.7B-shape layer",
@@ -317,7 +323,8 @@ def main():
                             (" + %d generation steps" % T if T else "")) if L == 1
                    else ("%d generation steps x %d resident layer caches (prompt phase done before "
                          "the clock starts)" % (T, L)),
-                   "launch": "eager" if graph is None else "hip-graph replay"},
+                   "launch": "eager" if graph is None else "hip-graph replay",
+                   "kv_bits": args.kv_bits or 8 * esize},
         "prefill_ms": min(prefill_ms) if L == 1 else None,
     }
     if attn_ms is not None:
@@ -351,8 +358,9 @@ def main():
         # the dominant kernel: the generation step, HBM-bound
         rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": achieved / HBM_PEAK_GBS,
-                           "traffic": PROFILED_TRAFFIC_BYTES.get(w.name),
-                           "kernel": "decode_resident_kernel", "bytes_per_launch": bytes_per_launch,
+                           "traffic": PROFILED_TRAFFIC_BYTES.get(w.name) if args.kv_bits == 0 else None,
+                           "kernel": "decode_resident_kernel" if args.kv_bits == 0 else "decode_q4_kernel",
+                           "bytes_per_launch": bytes_per_launch,
                            "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager}
         rec["decode_tokens_per_s"] = B / (dec_us * L * 1e-6)
         if mfma_roofline is not None:

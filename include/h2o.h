@@ -32,6 +32,8 @@
  *                                                  by the slot, -1 = free
  *     Which slot holds which token is an implementation detail: only the set
  *     of positions is meaningful.
+ *     With cfg.kv_bits = 4 the cached K and V are stored as 4-bit codes instead
+ *     (see h2o_config); everything the caller passes in stays in cfg.dtype.
  *   - positions count tokens from 0; `t` = number of tokens seen so far is the
  *     same for all heads (prompts are padded to one length, Sec. 5.3) and is
  *     tracked on the host handle;
@@ -71,6 +73,30 @@ typedef enum h2o_rank { H2O_RANK_ACCUMULATED = 0, H2O_RANK_AVERAGED = 1 } h2o_ra
 #define H2O_MAX_BUDGET 4096
 #define H2O_MAX_PROMPT 65536
 
+/*
+ * 4-bit cache storage (Sec. 5.4, "compatible with quantization"; App. on the
+ * throughput of H2O combined with quantisation).  The paper names the
+ * group-wise min-max quantiser of the serving system it builds on and prints
+ * no formula; the published one is used.  Along head_dim, per group of
+ * H2O_Q4_GROUP consecutive elements of a row:
+ *     mn = min, mx = max, scale = (mx - mn) / 15,
+ *     code_i = clamp(round_half_even((x_i - mn) / scale), 0, 15)   (scale = 0: 0),
+ *     stored value = mn + code_i * scale,
+ * every operation being one binary32 operation.  A row is quantised when it
+ * enters the cache: the rows kept by the prompt compression, and the new token
+ * after its own generation step (in that step it attends to itself with its
+ * unquantised key and value).  Scores, ranking and eviction are unchanged.
+ * A stored K (or V) row is head_dim/2 bytes of codes (element e in bits
+ * 4*(e%8) .. 4*(e%8)+3 of the little-endian 32-bit word e/8) followed by
+ * head_dim/64 pairs of floats (scale, min), padded to a multiple of 16 bytes:
+ * H2O_Q4_ROW_BYTES(head_dim) = 80 for 128, 48 for 64 (against 256 and 128 bytes
+ * of a 16-bit row).  Limits: heavy + recent <= H2O_Q4_MAX_BUDGET; no chunked
+ * prompt processing (h2o_prefill_chunk) on such a cache.
+ */
+#define H2O_Q4_GROUP 64
+#define H2O_Q4_ROW_BYTES(head_dim) ((head_dim) / 2 + 16)
+#define H2O_Q4_MAX_BUDGET 2048
+
 typedef struct h2o_config {
     int32_t batch;      /* B  >= 1 */
     int32_t heads;      /* Hh >= 1 */
@@ -80,6 +106,7 @@ typedef struct h2o_config {
     int32_t dtype;      /* h2o_dtype of Q/K/V/q/k/v/out and of the cached K/V */
     float scale;        /* logit scale; 0 selects 1/sqrt(head_dim) */
     int32_t rank;       /* h2o_rank; 0 = the method's accumulated score */
+    int32_t kv_bits;    /* cached K/V storage: 0 = elements of `dtype`, 4 = 4-bit codes */
 } h2o_config;
 
 typedef struct h2o_cache h2o_cache;   /* opaque host-side handle */
@@ -242,8 +269,9 @@ int h2o_cache_snapshot(const h2o_cache *cache, int32_t *pos_out, float *acc_out,
 
 /*
  * Loads a complete cache state (checkpoint restore; also how tests start a
- * generation from a state computed elsewhere): K, V [batch, heads, k, head_dim],
- * acc, pos [batch, heads, k] are copied in and t is set to `tokens_seen`.
+ * generation from a state computed elsewhere): K, V [batch, heads, k, head_dim]
+ * (with kv_bits = 4: [batch, heads, k, H2O_Q4_ROW_BYTES] bytes in the stored
+ * layout), acc, pos [batch, heads, k] are copied in and t is set to `tokens_seen`.
  * Every pos must be -1 or in [0, tokens_seen) and unique within a head (not
  * checked on the device).  Errors: EINVAL, EHIP.
  */

@@ -37,7 +37,7 @@ EXPORTS = (
 class h2o_config(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("heavy", ctypes.c_int32), ("recent", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("scale", ctypes.c_float), ("rank", ctypes.c_int32)]
+                ("scale", ctypes.c_float), ("rank", ctypes.c_int32), ("kv_bits", ctypes.c_int32)]
 
 
 class H2OError(RuntimeError):
@@ -104,11 +104,31 @@ def _check(rc: int, where: str) -> None:
         raise H2OError(rc, where)
 
 
-def make_config(batch, heads, head_dim, heavy, recent, dtype, scale=0.0, rank=0) -> h2o_config:
+H2O_Q4_GROUP = 64
+H2O_Q4_MAX_BUDGET = 2048
+
+
+def q4_row_bytes(head_dim: int) -> int:
+    """Bytes of one cached K (or V) row in 4-bit storage: codes, then (scale, min) pairs."""
+    return head_dim // 2 + 16
+
+
+def unpack_q4_rows(rows: torch.Tensor, head_dim: int):
+    """Splits stored rows [..., row bytes] (uint8) into codes [..., head_dim] (uint8,
+    one per element) and parameters [..., head_dim / 64, 2] (float32: scale, min)."""
+    cb = head_dim // 2
+    packed = rows[..., :cb]
+    codes = torch.stack((packed & 15, packed >> 4), dim=-1).reshape(*rows.shape[:-1], head_dim)
+    ng = head_dim // H2O_Q4_GROUP
+    par = rows[..., cb:cb + 8 * ng].contiguous().view(torch.float32).reshape(*rows.shape[:-1], ng, 2)
+    return codes, par
+
+
+def make_config(batch, heads, head_dim, heavy, recent, dtype, scale=0.0, rank=0, kv_bits=0) -> h2o_config:
     if isinstance(dtype, torch.dtype):
         dtype = DTYPES[dtype]
     return h2o_config(int(batch), int(heads), int(head_dim), int(heavy), int(recent), int(dtype),
-                      float(scale), int(rank))
+                      float(scale), int(rank), int(kv_bits))
 
 
 def h2o_status_str(status: int) -> str:
@@ -215,8 +235,8 @@ class H2OCache:
     one cache; methods forward to the entry points of the same name."""
 
     def __init__(self, batch, heads, head_dim, heavy, recent, dtype=torch.float16, scale=0.0,
-                 device="cuda", stream=None, rank=0):
-        self.cfg = make_config(batch, heads, head_dim, heavy, recent, dtype, scale, rank)
+                 device="cuda", stream=None, rank=0, kv_bits=0):
+        self.cfg = make_config(batch, heads, head_dim, heavy, recent, dtype, scale, rank, kv_bits)
         self.dtype = dtype if isinstance(dtype, torch.dtype) else TORCH_DTYPES[dtype]
         self.device = torch.device(device)
         self.budget = int(heavy) + int(recent)
@@ -291,7 +311,8 @@ class H2OCache:
 
     def views(self):
         """Tensor views (K, V, acc, pos) of the cache's regions: K, V [B, Hh, k, d]
-        in the cache dtype, acc [B, Hh, k] float32, pos [B, Hh, k] int32.  They
+        in the cache dtype (4-bit storage: uint8 [B, Hh, k, row bytes], codes then
+        (scale, min) pairs), acc [B, Hh, k] float32, pos [B, Hh, k] int32.  They
         alias the cache memory (for inspection and checkpointing)."""
         B, Hh = self.shape_heads
         d, k = self.cfg.head_dim, self.budget
@@ -303,6 +324,12 @@ class H2OCache:
         def view(addr, nbytes, dtype, shape):
             off = addr - base
             return self.mem[off:off + nbytes].view(dtype).view(shape)
+        if self.cfg.kv_bits == 4:
+            rowb = q4_row_bytes(d)
+            return (view(kaddr, cnt * rowb, torch.uint8, (B, Hh, k, rowb)),
+                    view(vaddr, cnt * rowb, torch.uint8, (B, Hh, k, rowb)),
+                    view(aaddr, cnt * 4, torch.float32, (B, Hh, k)),
+                    view(paddr, cnt * 4, torch.int32, (B, Hh, k)))
         return (view(kaddr, cnt * d * es, self.dtype, (B, Hh, k, d)),
                 view(vaddr, cnt * d * es, self.dtype, (B, Hh, k, d)),
                 view(aaddr, cnt * 4, torch.float32, (B, Hh, k)),

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libh2o_hip.so")
 OBJ_DIR = os.path.join(PKG, "_build")
-SOURCES = ["h2o_api.hip", "decode_step.hip", "prefill_scores.hip", "prefill_attention.hip",
+SOURCES = ["h2o_api.hip", "decode_step.hip", "decode_step_q4.hip", "prefill_scores.hip", "prefill_attention.hip",
            "select_gather.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -20,6 +20,8 @@ int check_config(const h2o_config *c)
     if (c->head_dim != 64 && c->head_dim != 128) return H2O_EUNSUPPORTED;
     if ((int64_t)c->heavy + c->recent > H2O_MAX_BUDGET) return H2O_EUNSUPPORTED;
     if ((int64_t)c->batch * c->heads > (1 << 24)) return H2O_EUNSUPPORTED;
+    if (c->kv_bits != 0 && c->kv_bits != 4) return H2O_EINVAL;
+    if (c->kv_bits == 4 && (int64_t)c->heavy + c->recent > H2O_Q4_MAX_BUDGET) return H2O_EUNSUPPORTED;
     return H2O_OK;
 }
 
@@ -29,7 +31,7 @@ Layout layout_of(const h2o_config &c)
 {
     const size_t heads = (size_t)c.batch * c.heads, k = (size_t)c.heavy + c.recent;
     Layout l;
-    l.kv = align_up(heads * k * c.head_dim * h2o_esize(c.dtype), 256);
+    l.kv = align_up(heads * k * h2o_row_bytes(c), 256);
     l.acc_off = 2 * l.kv;
     l.pos_off = l.acc_off + align_up(heads * k * sizeof(float), 256);
     l.total = l.pos_off + align_up(heads * k * sizeof(int32_t), 256);
@@ -71,6 +73,7 @@ int h2o_cache_init(const h2o_config *cfg, void *dev_mem, size_t bytes, void *hip
     c->scale = h2o_scale_of(*cfg);
     c->k = cfg->heavy + cfg->recent;
     c->esize = h2o_esize(cfg->dtype);
+    c->rowb = h2o_row_bytes(*cfg);
     c->t = 0;
     c->sorted = true;
     char *base = static_cast<char *>(dev_mem);
@@ -78,7 +81,7 @@ int h2o_cache_init(const h2o_config *cfg, void *dev_mem, size_t bytes, void *hip
     c->V = base + l.kv;
     c->acc = reinterpret_cast<float *>(base + l.acc_off);
     c->pos = reinterpret_cast<int32_t *>(base + l.pos_off);
-    c->kv_bytes = (size_t)cfg->batch * cfg->heads * c->k * cfg->head_dim * c->esize;
+    c->kv_bytes = (size_t)cfg->batch * cfg->heads * c->k * c->rowb;
     const hipError_t e = h2o_launch_mark_free(*c, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) { delete c; return H2O_EHIP; }
     *out = c;
@@ -195,7 +198,7 @@ int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K,
 
 size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m)
 {
-    if (check_config(cfg) != H2O_OK || m < 1) return 0;
+    if (check_config(cfg) != H2O_OK || m < 1 || cfg->kv_bits != 0) return 0;
     const size_t k = (size_t)cfg->heavy + cfg->recent;
     if (k + (size_t)m > H2O_MAX_PROMPT) return 0;
     const size_t heads = (size_t)cfg->batch * cfg->heads, ncat = k + m;
@@ -210,6 +213,7 @@ int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void
 {
     if (!cache || !Q || !K || !V || !workspace || m < 1) return H2O_EINVAL;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(workspace)) return H2O_EINVAL;
+    if (cache->cfg.kv_bits != 0) return H2O_EUNSUPPORTED;   // cached rows would have to be dequantised
     if (!cache->sorted) return H2O_ESTATE;
     const h2o_config &cfg = cache->cfg;
     const int occ = cache->t < cache->k ? cache->t : cache->k;
@@ -247,8 +251,9 @@ int h2o_decode_step(h2o_cache *cache, const void *q, const void *k_new, const vo
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out))
         return H2O_EINVAL;
     if (cache->t >= 0x7ffffff0) return H2O_EUNSUPPORTED;
-    const hipError_t e =
-        h2o_launch_decode(*cache, q, k_new, v_new, out, static_cast<hipStream_t>(hip_stream));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = cache->cfg.kv_bits == 4 ? h2o_launch_decode_q4(*cache, q, k_new, v_new, out, st)
+                                                 : h2o_launch_decode(*cache, q, k_new, v_new, out, st);
     if (e != hipSuccess) return H2O_EHIP;
     // free slots fill in index order (positions stay ascending); an eviction
     // overwrites a slot in the middle

@@ -9,7 +9,8 @@ struct h2o_cache {
     h2o_config cfg;
     double scale;      // logit scale actually used (cfg.scale, or 1/sqrt(d) in double)
     int k;             // heavy + recent
-    int esize;         // bytes per element of K/V
+    int esize;         // bytes per element of Q/K/V/q/k/v/out
+    int rowb;          // bytes of one cached K (or V) row as stored
     int t;             // tokens seen so far
     bool sorted;       // occupied slots hold ascending positions (true until a step evicts)
     char *K;           // [B*Hh][k][d]
@@ -20,6 +21,10 @@ struct h2o_cache {
 };
 
 static inline int h2o_esize(int dtype) { return dtype == H2O_F32 ? 4 : 2; }
+static inline int h2o_row_bytes(const h2o_config &c)
+{
+    return c.kv_bits == 4 ? H2O_Q4_ROW_BYTES(c.head_dim) : c.head_dim * h2o_esize(c.dtype);
+}
 static inline double h2o_scale_of(const h2o_config &c)
 {
     return c.scale != 0.0f ? (double)c.scale : 1.0 / sqrt((double)c.head_dim);
@@ -29,6 +34,9 @@ static inline double h2o_scale_of(const h2o_config &c)
 hipError_t h2o_launch_mark_free(const h2o_cache &c, hipStream_t st);
 hipError_t h2o_launch_decode(const h2o_cache &c, const void *q, const void *k_new,
                              const void *v_new, void *out, hipStream_t st);
+// the same step over a cache that stores 4-bit codes
+hipError_t h2o_launch_decode_q4(const h2o_cache &c, const void *q, const void *k_new,
+                                const void *v_new, void *out, hipStream_t st);
 // prompt scoring: the nq queries (rows of Q) are the last nq positions of the nk
 // keys; lse [B*Hh][nq] = log2 of the row normalisers, colsum [B*Hh][nk]
 hipError_t h2o_launch_prefill_lse(const h2o_config &cfg, double scale, const void *Q,

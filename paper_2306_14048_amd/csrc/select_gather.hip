@@ -10,7 +10,7 @@
 // on the order-preserving integer image of the scores finds the threshold, the
 // positions of equal-score tokens break the tie at the threshold, a block scan
 // assigns slots, then all threads copy rows with 128-bit accesses.
-#include "h2o_internal.h"
+#include "wave_ops.h"
 
 namespace {
 
@@ -51,7 +51,10 @@ __device__ inline int block_exclusive_scan(int v, int *scratch, int &total)
 // Entry j of a head's n candidates is the token at position pos_in[j] (ascending;
 // pos_in == nullptr: position j) with score base[j] + score[j] (base == nullptr:
 // score[j]); t_new = number of tokens seen once these are stored.
-template <int ROWB>
+// QDT < 0: the cache stores rows as they are (ROWB bytes each).  QDT = an element
+// type: the cache stores 4-bit codes and the kept rows (ROWB bytes of QDT
+// elements) are quantised on their way in.
+template <int ROWB, int QDT>
 __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     const char *__restrict__ Kp, const char *__restrict__ Vp, const float *__restrict__ score,
     const float *__restrict__ base, const int32_t *__restrict__ pos_in, int n, int t_new,
@@ -175,6 +178,41 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
         pos_g[hoff + s] = j >= 0 ? pos_of(j) : -1;
         acc_g[hoff + s] = j >= 0 ? sc_of(j) : 0.f;
     }
+    if constexpr (QDT >= 0) {
+        // quantising gather: D/8 lanes per row, 8 elements each; an aligned group of 8
+        // lanes is one group of 64 elements
+        using T = typename Elem<QDT>::T;
+        constexpr int D = ROWB / (int)sizeof(T);
+        constexpr int QL = D / 8;
+        constexpr int CODEB = D / 2;
+        constexpr unsigned QROWB = H2O_Q4_ROW_BYTES(D);
+        constexpr int RPR = SG_NT / QL;              // rows per round
+        const int l = tid % QL, rsub = tid / QL;
+        const size_t pbase = (size_t)head * n * ROWB;
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        // every lane runs every round (the reductions inside the quantiser span lanes)
+        for (int s0 = 0; s0 < k; s0 += RPR) {
+            const int s = s0 + rsub;
+            const int j = s < k ? sel_l[s] : -1;
+            const size_t off = pbase + (size_t)max(j, 0) * ROWB;
+            float kx[8], vx[8];
+            load8<QDT>(reinterpret_cast<const T *>(Kp + off) + l * 8, kx);
+            load8<QDT>(reinterpret_cast<const T *>(Vp + off) + l * 8, vx);
+            float ks, km, vs, vm;
+            const unsigned kw = q4_quantise8(kx, ks, km);
+            const unsigned vw = q4_quantise8(vx, vs, vm);
+            if (j >= 0) {
+                char *kr = Kc + (hoff + s) * QROWB, *vr = Vc + (hoff + s) * QROWB;
+                *reinterpret_cast<unsigned *>(kr + l * 4) = kw;
+                *reinterpret_cast<unsigned *>(vr + l * 4) = vw;
+                if ((l & 7) == 0) {
+                    *reinterpret_cast<f32x2 *>(kr + CODEB + (l / 8) * 8) = f32x2{ks, km};
+                    *reinterpret_cast<f32x2 *>(vr + CODEB + (l / 8) * 8) = f32x2{vs, vm};
+                }
+            }
+        }
+        return;
+    }
     // gather rows: LPR lanes copy one row of ROWB bytes
     constexpr int LPR = ROWB / 16;
     constexpr int ROWS_PER_ROUND = SG_NT / LPR;
@@ -211,6 +249,17 @@ __global__ void mark_free_kernel(float *__restrict__ acc, int32_t *__restrict__ 
     if (i < count) { acc[i] = 0.f; pos[i] = -1; }
 }
 
+// Slot 0 of every head is what a step on an empty cache reads in place of the
+// rows that do not exist yet (with weight zero): it must hold finite numbers.
+__global__ void zero_first_rows_kernel(char *__restrict__ K, char *__restrict__ V, int k, int rowb)
+{
+    const size_t base = (size_t)blockIdx.x * k * rowb;
+    for (int b = threadIdx.x * 4; b < rowb; b += blockDim.x * 4) {
+        *reinterpret_cast<unsigned *>(K + base + b) = 0u;
+        *reinterpret_cast<unsigned *>(V + base + b) = 0u;
+    }
+}
+
 }  // namespace
 
 hipError_t h2o_launch_mark_free(const h2o_cache &c, hipStream_t st)
@@ -218,6 +267,8 @@ hipError_t h2o_launch_mark_free(const h2o_cache &c, hipStream_t st)
     const size_t count = (size_t)c.cfg.batch * c.cfg.heads * c.k;
     const unsigned blocks = (unsigned)((count + 255) / 256);
     hipLaunchKernelGGL(mark_free_kernel, dim3(blocks), dim3(256), 0, st, c.acc, c.pos, count);
+    hipLaunchKernelGGL(zero_first_rows_kernel, dim3(c.cfg.batch * c.cfg.heads), dim3(64), 0, st,
+                       c.K, c.V, c.k, c.rowb);
     return hipGetLastError();
 }
 
@@ -229,14 +280,23 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
     const int rowb = c.cfg.head_dim * c.esize;
     const size_t smem = (size_t)c.k * sizeof(int);
     const char *Kp = static_cast<const char *>(K), *Vp = static_cast<const char *>(V);
-#define H2O_SG(RB)                                                                              \
-    hipLaunchKernelGGL((select_gather_kernel<RB>), dim3(heads), dim3(SG_NT), smem, st, Kp, Vp,   \
-                       score, base, pos_in, n, t_new, c.K, c.V, c.acc, c.pos, c.k, c.cfg.heavy, \
-                       c.cfg.recent, c.cfg.rank)
+#define H2O_SG(RB, QDT)                                                                         \
+    hipLaunchKernelGGL((select_gather_kernel<RB, QDT>), dim3(heads), dim3(SG_NT), smem, st, Kp, \
+                       Vp, score, base, pos_in, n, t_new, c.K, c.V, c.acc, c.pos, c.k,          \
+                       c.cfg.heavy, c.cfg.recent, c.cfg.rank)
+    if (c.cfg.kv_bits == 4) {
+        const int d = c.cfg.head_dim;
+        switch (c.cfg.dtype) {
+        case H2O_F32: if (d == 64) H2O_SG(256, H2O_F32); else H2O_SG(512, H2O_F32); break;
+        case H2O_F16: if (d == 64) H2O_SG(128, H2O_F16); else H2O_SG(256, H2O_F16); break;
+        default: if (d == 64) H2O_SG(128, H2O_BF16); else H2O_SG(256, H2O_BF16); break;
+        }
+        return hipGetLastError();
+    }
     switch (rowb) {
-    case 128: H2O_SG(128); break;
-    case 256: H2O_SG(256); break;
-    case 512: H2O_SG(512); break;
+    case 128: H2O_SG(128, -1); break;
+    case 256: H2O_SG(256, -1); break;
+    case 512: H2O_SG(512, -1); break;
     default: return hipErrorInvalidValue;
     }
 #undef H2O_SG

@@ -61,7 +61,7 @@ class DecodeStats:
 
 
 def oracle_prefill_heads(Q, K, V, heads, heavy, recent, scale, cap, score_f32=True, threads=None,
-                         policy=0):
+                         policy=0, kv_bits=0):
     """Runs the oracle's prompt phase for the listed (b, h) pairs.
     Q, K, V: torch tensors [B, Hh, n, d] (any device).  Returns
     ({(b, h): OracleHead}, {(b, h): colsum float64[n]})."""
@@ -69,7 +69,7 @@ def oracle_prefill_heads(Q, K, V, heads, heavy, recent, scale, cap, score_f32=Tr
 
     def one(bh):
         b, h = bh
-        o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=cap, policy=policy)
+        o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=cap, policy=policy, kv_bits=kv_bits)
         col, _ = o.prefill(host64(Q[b, h]), host64(K[b, h]), host64(V[b, h]))
         return o, col
 

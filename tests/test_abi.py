@@ -49,7 +49,17 @@ def test_size_queries_and_validation(hb):
         assert hb.h2o_cache_bytes(c) == 0
     assert hb.h2o_cache_bytes(hb.make_config(16, 32, 128, 205, 205, hb.H2O_F16, rank=hb.H2O_RANK_AVERAGED)) \
         == 2 * kv + 2 * meta
-    assert ctypes.sizeof(hb.h2o_config) == 32
+    assert ctypes.sizeof(hb.h2o_config) == 36
+    # 4-bit storage: rows of head_dim/2 code bytes + 16 bytes of (scale, min) pairs
+    q4 = hb.make_config(16, 32, 128, 205, 205, hb.H2O_F16, kv_bits=4)
+    assert hb.h2o_cache_bytes(q4) == 2 * 16 * 32 * 410 * 80 + 2 * meta
+    assert hb.h2o_cache_bytes(hb.make_config(2, 2, 64, 8, 8, hb.H2O_BF16, kv_bits=4)) == \
+        2 * 2 * 2 * 16 * 48 + 2 * 256
+    assert hb.h2o_cache_bytes(hb.make_config(1, 1, 128, 8, 8, hb.H2O_F16, kv_bits=8)) == 0
+    assert hb.h2o_cache_bytes(hb.make_config(1, 1, 128, 1024, 1024, hb.H2O_F16, kv_bits=4)) > 0
+    assert hb.h2o_cache_bytes(hb.make_config(1, 1, 128, 1025, 1024, hb.H2O_F16, kv_bits=4)) == 0
+    assert hb.h2o_prefill_chunk_workspace_bytes(q4, 512) == 0      # no chunked prompt on a 4-bit cache
+    assert hb.q4_row_bytes(128) == 80 and hb.q4_row_bytes(64) == 48
     assert hb.h2o_prefill_workspace_bytes(ok, 0) == 0
     assert hb.h2o_prefill_workspace_bytes(ok, hb.H2O_MAX_PROMPT + 1) == 0
     # transposed V padded to whole 64-key tiles, then the scoring scratch
