@@ -62,13 +62,17 @@ __device__ inline uint4 load_codes_stream(const char *base, unsigned byte_off)
 __host__ __device__ constexpr int code_bit(int j) { return j < 5 ? 4 * j : 4 * (j - 3); }
 
 // Registers: a lane keeps its 32 elements of q as doubles (64 registers) next to
-// the rounds in flight (6 registers each).  With the minimum number of rounds that
-// gives every lane a slot this just fits the 128 registers of two 8-wave (or four
-// 4-wave) workgroups per CU, which is why everything that is only needed after the
-// key pass (slot bookkeeping, the new token's stored form) is requested after it;
-// deeper rings run one workgroup per CU.
+// the rounds in flight (7 registers each), which is why everything that is only
+// needed after the key pass (slot bookkeeping, the new token once more) is
+// requested after it, and why no loaded value may ever be spilled: a spill of a
+// register a load is still writing waits for the whole stream.  Four-wave
+// workgroups: 256 slots fit 128 registers (four workgroups per CU), 512 slots 168
+// (three per CU); deeper rings run at two waves per SIMD.  Eight waves per head
+// with half the rounds each were measured slower (more waves redo the softmax and
+// bookkeeping than the shorter rounds save).
 template <int DT, int D, int NW, int U>
-__global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void decode_q4_kernel(
+__global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : (NW == 4 && U * (64 / (D / 32)) == 128) ? 3 : 2)
+void decode_q4_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
@@ -76,7 +80,6 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
 {
     using E = Elem<DT>;
     using T = typename E::T;
-    constexpr int EPL = E::EPL;                 // elements per 16-byte load of an input vector
     constexpr int CODEB = D / 2;                // bytes of codes per row
     constexpr unsigned ROWB = H2O_Q4_ROW_BYTES(D);
     constexpr int LPR = D / 32;                 // lanes per row, 32 codes each
@@ -85,7 +88,9 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
     constexpr int OWN = U * RPW;                // slots a wave owns
     constexpr int SPL = OWN / 64;               // ... per lane
     constexpr int QL = D / 8;                   // lanes holding the new key, 8 elements each
-    constexpr int NQ = 32 / EPL;                // 16-byte loads per lane for its 32 elements of q
+    constexpr int QPITCH = 34;                  // doubles per 32-element slice of q in LDS (bank spread)
+    constexpr int OPITCH = D + 4;               // floats per row of partial outputs in LDS (bank spread)
+    static_assert(NW * 64 >= D, "one thread per element of q");
     static_assert(OWN % 64 == 0 && SPL >= 1, "whole slots per lane");
     static_assert(D == 64 || D == 128, "head dimension");
 
@@ -99,8 +104,11 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
     double *red_sum = s_l + NW * OWN;                                  // [NW]
     double *red_max = red_sum + NW;                                    // [NW] (overflow path)
     double *red_key = red_max + NW;                                    // [NW]
-    float *p_l = reinterpret_cast<float *>(red_key + NW);              // [NW][OWN]
-    float *o_l = p_l + NW * OWN;                                       // [NW][4][D]
+    double *qd_l = red_key + NW;                                       // [LPR][QPITCH] q as doubles
+    float *p_l = reinterpret_cast<float *>(qd_l + LPR * QPITCH);       // [NW][OWN]
+    float *fix_l = p_l + NW * OWN;                                     // [NW][4]
+    unsigned *new_l = reinterpret_cast<unsigned *>(fix_l + NW * 4);    // [3][32] the new token as stored
+    float *o_l = reinterpret_cast<float *>(new_l + 96);                // [NW * RPW][OPITCH]
     double *s_w = s_l + wave * OWN;
     float *p_w = p_l + wave * OWN;
 
@@ -123,10 +131,7 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
     }
 
     // ---- requests: q, the new token, then the whole key stream ------------------
-    uint4 qraw[NQ];
-#pragma unroll
-    for (int i = 0; i < NQ; ++i)
-        qraw[i] = *reinterpret_cast<const uint4 *>(qh + li * 32 + i * EPL);
+    const T q_elem = qh[tid % D];               // threads [0, D) widen q once for the workgroup
     // 8 elements of q and of the new key per lane (lanes [0, QL) cover the row): the token's own logit
     const int e8 = (lane % QL) * 8;
     float q8[8], k8[8];
@@ -139,7 +144,7 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
     f32x2 par[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        off[u] = (unsigned)min(u * RPI + row0, last) * ROWB + (unsigned)li * 16u;
+        off[u] = __umul24((unsigned)min(u * RPI + row0, last), ROWB) + (unsigned)li * 16u;
         buf[u] = load_codes_stream(Kb, off[u]);
         par[u] = load_pair_stream(Kb, off[u] + to_pair);
     }
@@ -154,16 +159,17 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
         s_self = lane_value(group_sum<QL>(a), 0) * scale;     // lanes [0, QL) hold q.k_new
     }
 
-    // ---- this lane's 32 elements of q, widened exactly ---------------------------
+    // ---- this lane's 32 elements of q, widened exactly (once per workgroup, via LDS) ---
+    if (tid < D) qd_l[(tid / 32) * QPITCH + (tid % 32)] = (double)E::to_f(q_elem);
+    lds_barrier();
     double qd[32];
     double qsum = 0.0, surplus = 0.0;           // sum q_e and sum q_e 2^(20 - bit(e))
     {
 #pragma unroll
-        for (int i = 0; i < NQ; ++i) {
-            float f[EPL];
-            piece_to_float<DT>(qraw[i], f);
-#pragma unroll
-            for (int j = 0; j < EPL; ++j) qd[i * EPL + j] = (double)f[j];
+        for (int i = 0; i < 32; i += 2) {
+            const double2 two = *reinterpret_cast<const double2 *>(qd_l + li * QPITCH + i);
+            qd[i] = two.x;
+            qd[i + 1] = two.y;
         }
         double by_bit[5] = {0.0, 0.0, 0.0, 0.0, 0.0};        // codes that sit at bit 0, 4, 8, 12, 16
 #pragma unroll
@@ -209,8 +215,12 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
             const double tot = row_lanes_sum<LPR>(part);
             if (li == 0) s_w[u * RPW + sub] = tot * scale;
         }
-        buf[u] = load_codes_stream(Vb, off[u]);               // the value row takes the registers
-        par[u] = load_pair_stream(Vb, off[u] + to_pair);
+        // the value row takes the registers; the pair's offset is worked out here, from a
+        // copy the compiler cannot see through, so that it is not kept for every round
+        unsigned o = off[u];
+        asm volatile("" : "+v"(o));
+        buf[u] = load_codes_stream(Vb, o);
+        par[u] = load_pair_stream(Vb, o + to_pair);
         __builtin_amdgcn_sched_barrier(0);
     }
     // What is needed after the value pass, requested behind the value stream (loads
@@ -318,28 +328,33 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
         __builtin_amdgcn_sched_barrier(0);
     }
     {
-        // settle the two constants, add up the rows of each 16-lane group, hand the
-        // group's totals to LDS: o_l[wave][group of 16][column]
-        const float fix = msum - 16.f * wsum;
+        // every lane hands its 32 partial columns to LDS (o_l[row of the round][column]);
+        // the two constants, which belong to all 32 columns alike, are added up over
+        // the wave's rows first: fix_l[wave][li]
+        float *dst = o_l + (wave * RPW + sub) * OPITCH + li * 32;
 #pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            float v = o[i] + fix;
-            v += dpp_f<DPP_ROR8>(v);
-            v += dpp_f<DPP_ROR4>(v);
-            if (LPR == 2) v += dpp_f<DPP_ROR2>(v);
-            o[i] = v;
-        }
-        if ((lane & 15) < LPR) {
-            float *dst = o_l + (wave * 4 + (lane >> 4)) * D + li * 32;
-#pragma unroll
-            for (int i = 0; i < 32; i += 4)
-                *reinterpret_cast<float4 *>(dst + i) = make_float4(o[i], o[i + 1], o[i + 2], o[i + 3]);
-        }
+        for (int i = 0; i < 32; i += 4)
+            *reinterpret_cast<float4 *>(dst + i) = make_float4(o[i], o[i + 1], o[i + 2], o[i + 3]);
+        float fix = msum - 16.f * wsum;
+        fix += dpp_f<DPP_ROR8>(fix);
+        fix += dpp_f<DPP_ROR4>(fix);
+        if (LPR == 2) fix += dpp_f<DPP_ROR2>(fix);
+        fix += __shfl_xor(fix, 16, 64);
+        fix += __shfl_xor(fix, 32, 64);
+        if (lane < LPR) fix_l[wave * 4 + lane] = fix;
     }
 
-    // ---- the new token as it will be stored -----------------------------------------
-    float new_scale, new_min;
-    const unsigned new_word = q4_quantise8(n8, new_scale, new_min);
+    // ---- the new token as it will be stored (one wave works it out for whichever
+    // wave turns out to own the slot) ---------------------------------------------------
+    if (wave == 0) {
+        float new_scale, new_min;
+        const unsigned new_word = q4_quantise8(n8, new_scale, new_min);
+        if (lane < 32) {
+            new_l[lane] = new_word;
+            new_l[32 + lane] = __float_as_uint(new_scale);
+            new_l[64 + lane] = __float_as_uint(new_min);
+        }
+    }
 
     // ---- score update (Algorithm 2, accumulate line: binary32 add of the binary32
     // probability) and the eviction candidate: smallest (rank value, position) outside
@@ -364,10 +379,15 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
 
     // ---- write-back ---------------------------------------------------------------------
     if (tid < D) {
-        float r = p_self * E::to_f(v_self_raw);
+        float r0 = p_self * E::to_f(v_self_raw), r1 = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW * 4; ++w) r += o_l[w * D + tid];
-        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r);
+        for (int w = 0; w < NW; ++w) r1 += fix_l[w * 4 + tid / 32];
+#pragma unroll 8
+        for (int row = 0; row < NW * RPW; row += 2) {
+            r0 += o_l[row * OPITCH + tid];
+            r1 += o_l[(row + 1) * OPITCH + tid];
+        }
+        reinterpret_cast<T *>(out_g)[(size_t)head * D + tid] = E::from_f(r0 + r1);
     }
     int tslot = -1;          // wave-uniform: the slot this wave has to fill, if any
     int lost_slot = -1;      // per lane: its slot that has just been evicted
@@ -395,9 +415,10 @@ __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : 2) void de
         if (lane < 2 * QL) {
             char *row = (lane < QL ? Kb : Vb) + (size_t)tslot * ROWB;
             const int l = lane % QL;
-            *reinterpret_cast<unsigned *>(row + l * 4) = new_word;
+            *reinterpret_cast<unsigned *>(row + l * 4) = new_l[lane];
             if ((l & 7) == 0)
-                *reinterpret_cast<f32x2 *>(row + CODEB + (l / 8) * 8) = f32x2{new_scale, new_min};
+                *reinterpret_cast<f32x2 *>(row + CODEB + (l / 8) * 8) =
+                    f32x2{__uint_as_float(new_l[32 + lane]), __uint_as_float(new_l[64 + lane])};
         }
     }
 }
@@ -411,12 +432,21 @@ template <int DT, int D, int NW, int U>
 hipError_t launch_q4(const h2o_cache &c, const void *q, const void *kn, const void *vn, void *out,
                      hipStream_t st)
 {
-    constexpr int OWN = U * (64 / (D / 32));
-    constexpr size_t smem = (size_t)NW * OWN * 8 + (size_t)NW * 24 + (size_t)NW * OWN * 4 +
-                            (size_t)NW * 4 * D * 4 + 16;
-    static_assert(smem <= 48 * 1024, "fits the default dynamic LDS limit");
-    hipLaunchKernelGGL((decode_q4_kernel<DT, D, NW, U>), dim3(c.cfg.batch * c.cfg.heads),
-                       dim3(NW * 64), smem, st, H2O_DECODE_ARGS);
+    constexpr int LPR = D / 32, RPW = 64 / LPR, OWN = U * RPW;
+    constexpr size_t smem = (size_t)NW * OWN * 8 + (size_t)NW * 24 + (size_t)LPR * 34 * 8 +
+                            (size_t)NW * OWN * 4 + (size_t)NW * 16 + 384 +
+                            (size_t)NW * RPW * (D + 4) * 4 + 16;
+    auto kern = decode_q4_kernel<DT, D, NW, U>;
+    if (smem > 48 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st, H2O_DECODE_ARGS);
     return hipGetLastError();
 }
 
