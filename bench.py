@@ -141,6 +141,8 @@ def main():
                          "'chunked' = the prompt in chunks of --chunk tokens, each scored against "
                          "cache + chunk and compressed to the budget (bounded memory)")
     ap.add_argument("--chunk", type=int, default=1024, help="chunk length for --prompt chunked")
+    ap.add_argument("--chunk-output", action="store_true",
+                    help="--prompt chunked: also produce every chunk's attention output")
     ap.add_argument("--kv-bits", type=int, default=0, choices=(0, 4),
                     help="cache storage: 0 = the workload's element type, 4 = 4-bit group-wise codes")
     ap.add_argument("--decode-steps", type=int, default=0,
@@ -178,11 +180,14 @@ def main():
             ws = torch.empty(hb.h2o_prefill_attention_workspace_bytes(cache.cfg, n),
                              dtype=torch.uint8, device=dev)
             attn_out = torch.empty_like(Q)
-        chunks = []
+        chunks, chunk_out = [], None
         if args.prompt == "chunked":
             # the chunk entry point takes [B, Hh, m, d] blocks: cut the prompt up before the clock starts
             m = max(1, min(args.chunk, n))
-            ws = torch.empty(hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, m), dtype=torch.uint8, device=dev)
+            ws = torch.empty(hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, m, args.chunk_output),
+                             dtype=torch.uint8, device=dev)
+            if args.chunk_output:
+                chunk_out = torch.empty((B, Hh, m, d), dtype=w.dtype, device=dev).data_ptr()
             for t0 in range(0, n, m):
                 chunks.append(tuple(x[:, :, t0:t0 + m].contiguous() for x in (Q, K, V)))
         Qp, Kp, Vp, wsp, wsn = Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel()
@@ -226,7 +231,7 @@ def main():
         elif L == 1 and args.prompt == "chunked":
             for (cq, ck, cv) in chunks:
                 hb.h2o_prefill_chunk(ptrs[0][0], cq.data_ptr(), ck.data_ptr(), cv.data_ptr(),
-                                     cq.shape[2], wsp, wsn, sp)
+                                     cq.shape[2], wsp, wsn, chunk_out, sp)
         elif L == 1:
             hb.h2o_prefill_scores(ptrs[0][0], Qp, Kp, Vp, n, wsp, wsn, None, sp)
         if timed_events:

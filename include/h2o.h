@@ -175,9 +175,10 @@ int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K,
 
 /* Device bytes of scratch h2o_prefill_chunk needs for chunks of up to m tokens
  * (cache + chunk as one candidate list: K and V rows, old scores, positions,
- * column sums, row statistics).  Returns 0 for invalid arguments and when
- * heavy + recent + m exceeds H2O_MAX_PROMPT. */
-size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m);
+ * column sums, row statistics; with_output != 0: also the transposed V the
+ * attention output needs).  Returns 0 for invalid arguments, when heavy + recent
+ * + m exceeds H2O_MAX_PROMPT, and for with_output on a binary32 configuration. */
+size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m, int32_t with_output);
 
 /*
  * The next m prompt tokens as one chunk: prompt processing with bounded memory.
@@ -192,14 +193,18 @@ size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m);
  * ones).  m = 1 is what h2o_decode_step computes (without the output); one
  * chunk holding the whole prompt on an empty cache is h2o_prefill_scores.
  *   Q, K, V   [batch, heads, m, head_dim] in cfg.dtype
- *   workspace >= h2o_prefill_chunk_workspace_bytes(cfg, m)
+ *   workspace >= h2o_prefill_chunk_workspace_bytes(cfg, m, out != NULL)
+ *   out       NULL, or [batch, heads, m, head_dim] in cfg.dtype: the attention
+ *             output of the chunk's tokens (sum over cached and chunk tokens of
+ *             probability times value), which makes the call a layer's complete
+ *             attention for the chunk; 16-bit element types only
  * The cached tokens must sit in ascending position order, which holds after
  * h2o_cache_init / _reset / h2o_prefill_* and until a generation step evicts.
  * Then t becomes t + m.  Errors: EINVAL, EUNSUPPORTED, ENOMEM, ESTATE (slots no
  * longer in position order), EHIP.
  */
 int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void *V,
-                      int32_t m, void *workspace, size_t ws_bytes, void *hip_stream);
+                      int32_t m, void *workspace, size_t ws_bytes, void *out, void *hip_stream);
 
 /*
  * Device bytes of scratch h2o_prefill_attention / h2o_prefill_attention_scores

@@ -69,8 +69,8 @@ _lib.h2o_prefill_attention_workspace_bytes.argtypes = [_cfgp, _i32]
 _lib.h2o_prefill_attention.argtypes = [_cfgp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp, _vp]
 _lib.h2o_prefill_attention_scores.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp, _vp]
 _lib.h2o_prefill_chunk_workspace_bytes.restype = _sz
-_lib.h2o_prefill_chunk_workspace_bytes.argtypes = [_cfgp, _i32]
-_lib.h2o_prefill_chunk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
+_lib.h2o_prefill_chunk_workspace_bytes.argtypes = [_cfgp, _i32, _i32]
+_lib.h2o_prefill_chunk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
 _lib.h2o_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.h2o_cache_snapshot.argtypes = [_vp, _vp, _vp, _vp]
 _lib.h2o_cache_restore.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
@@ -194,13 +194,13 @@ def h2o_prefill_attention_scores(cache, Q, K, V, n, workspace, ws_bytes, out, co
            "h2o_prefill_attention_scores")
 
 
-def h2o_prefill_chunk_workspace_bytes(cfg: h2o_config, m: int) -> int:
-    return int(_lib.h2o_prefill_chunk_workspace_bytes(ctypes.byref(cfg), int(m)))
+def h2o_prefill_chunk_workspace_bytes(cfg: h2o_config, m: int, with_output: bool = False) -> int:
+    return int(_lib.h2o_prefill_chunk_workspace_bytes(ctypes.byref(cfg), int(m), 1 if with_output else 0))
 
 
-def h2o_prefill_chunk(cache, Q, K, V, m, workspace, ws_bytes, stream=None) -> None:
+def h2o_prefill_chunk(cache, Q, K, V, m, workspace, ws_bytes, out=None, stream=None) -> None:
     _check(_lib.h2o_prefill_chunk(cache, _ptr(Q), _ptr(K), _ptr(V), int(m), _ptr(workspace),
-                                  int(ws_bytes), _stream(stream)), "h2o_prefill_chunk")
+                                  int(ws_bytes), _ptr(out), _stream(stream)), "h2o_prefill_chunk")
 
 
 def h2o_decode_step(cache, q, k_new, v_new, out, stream=None) -> None:
@@ -279,15 +279,16 @@ class H2OCache:
         ws = self.workspace(n)
         h2o_prefill_scores(self.handle, Q, K, V, n, ws, ws.numel(), colsum_out, stream)
 
-    def prefill_chunk(self, Q, K, V, stream=None):
-        """The next Q.shape[-2] prompt tokens as one chunk ([batch, heads, m, head_dim], contiguous)."""
+    def prefill_chunk(self, Q, K, V, out=None, stream=None):
+        """The next Q.shape[-2] prompt tokens as one chunk ([batch, heads, m, head_dim],
+        contiguous); `out` (same shape) receives the chunk's attention output if given."""
         m = Q.shape[-2]
-        need = h2o_prefill_chunk_workspace_bytes(self.cfg, m)
+        need = h2o_prefill_chunk_workspace_bytes(self.cfg, m, out is not None)
         if need == 0:
             raise H2OError(H2O_EUNSUPPORTED, "h2o_prefill_chunk_workspace_bytes")
         if self._ws is None or self._ws.numel() < need:
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
-        h2o_prefill_chunk(self.handle, Q, K, V, m, self._ws, self._ws.numel(), stream)
+        h2o_prefill_chunk(self.handle, Q, K, V, m, self._ws, self._ws.numel(), out, stream)
 
     def prefill_select(self, K, V, score, stream=None):
         h2o_prefill_select(self.handle, K, V, score, K.shape[-2], stream)

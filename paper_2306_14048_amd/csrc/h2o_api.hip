@@ -173,7 +173,7 @@ int h2o_prefill_attention(const h2o_config *cfg, const void *Q, const void *K, c
     if (ws_bytes < h2o_prefill_attention_workspace_bytes(cfg, n)) return H2O_ENOMEM;
     char *ws = static_cast<char *>(workspace);
     float *lse2 = reinterpret_cast<float *>(ws + align_up(h2o_attn_vt_bytes(*cfg, n), 256));
-    return hip_rc(h2o_launch_prefill_attention(*cfg, h2o_scale_of(*cfg), Q, K, V, n, ws, lse2,
+    return hip_rc(h2o_launch_prefill_attention(*cfg, h2o_scale_of(*cfg), Q, K, V, n, n, ws, lse2,
                                                lse_out, out, static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -196,29 +196,34 @@ int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K,
     return h2o_prefill_select(cache, K, V, sums, n, hip_stream);
 }
 
-size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m)
+size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m, int32_t with_output)
 {
     if (check_config(cfg) != H2O_OK || m < 1 || cfg->kv_bits != 0) return 0;
+    if (with_output && cfg->dtype == H2O_F32) return 0;
     const size_t k = (size_t)cfg->heavy + cfg->recent;
     if (k + (size_t)m > H2O_MAX_PROMPT) return 0;
     const size_t heads = (size_t)cfg->batch * cfg->heads, ncat = k + m;
     const size_t rows = align_up(heads * ncat * cfg->head_dim * h2o_esize(cfg->dtype), 256);
     const size_t vec = align_up(heads * ncat * sizeof(float), 256);
     // K and V of cache + chunk, old scores, positions, column sums, row statistics
-    return 2 * rows + 3 * vec + align_up(heads * (size_t)m * sizeof(float), 256);
+    // (+ the transposed V of cache + chunk when the attention output is wanted)
+    return 2 * rows + 3 * vec + align_up(heads * (size_t)m * sizeof(float), 256) +
+           (with_output ? align_up(h2o_attn_vt_bytes(*cfg, (int)ncat), 256) : 0);
 }
 
 int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void *V, int32_t m,
-                      void *workspace, size_t ws_bytes, void *hip_stream)
+                      void *workspace, size_t ws_bytes, void *out, void *hip_stream)
 {
     if (!cache || !Q || !K || !V || !workspace || m < 1) return H2O_EINVAL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(workspace)) return H2O_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(workspace) || !aligned16(out))
+        return H2O_EINVAL;
     if (cache->cfg.kv_bits != 0) return H2O_EUNSUPPORTED;   // cached rows would have to be dequantised
+    if (out && cache->cfg.dtype == H2O_F32) return H2O_EUNSUPPORTED;
     if (!cache->sorted) return H2O_ESTATE;
     const h2o_config &cfg = cache->cfg;
     const int occ = cache->t < cache->k ? cache->t : cache->k;
     if ((int64_t)cache->k + m > H2O_MAX_PROMPT || (int64_t)cache->t + m >= 0x7ffffff0) return H2O_EUNSUPPORTED;
-    if (ws_bytes < h2o_prefill_chunk_workspace_bytes(&cfg, m)) return H2O_ENOMEM;
+    if (ws_bytes < h2o_prefill_chunk_workspace_bytes(&cfg, m, out != nullptr)) return H2O_ENOMEM;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const size_t heads = (size_t)cfg.batch * cfg.heads, ncat_max = (size_t)cache->k + m;
     const size_t rows = align_up(heads * ncat_max * cfg.head_dim * cache->esize, 256);
@@ -229,11 +234,14 @@ int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void
     int32_t *pos_cat = reinterpret_cast<int32_t *>(ws + 2 * rows + vec);
     float *colsum = reinterpret_cast<float *>(ws + 2 * rows + 2 * vec);
     float *lse = reinterpret_cast<float *>(ws + 2 * rows + 3 * vec);
+    char *vt = ws + 2 * rows + 3 * vec + align_up(heads * (size_t)m * sizeof(float), 256);
     const int ncat = occ + m;
     const double scale = h2o_scale_of(cfg);
     hipError_t e = h2o_launch_concat(*cache, K, V, m, occ, Kcat, Vcat, base, pos_cat, st);
     if (e != hipSuccess) return H2O_EHIP;
-    e = h2o_launch_prefill_lse(cfg, scale, Q, Kcat, m, ncat, lse, st);
+    // row statistics: a by-product of the attention output when that is wanted
+    e = out ? h2o_launch_prefill_attention(cfg, scale, Q, Kcat, Vcat, m, ncat, vt, lse, nullptr, out, st)
+            : h2o_launch_prefill_lse(cfg, scale, Q, Kcat, m, ncat, lse, st);
     if (e != hipSuccess) return H2O_EHIP;
     e = h2o_launch_prefill_colsum(cfg, scale, Q, Kcat, m, ncat, lse, colsum, st);
     if (e != hipSuccess) return H2O_EHIP;

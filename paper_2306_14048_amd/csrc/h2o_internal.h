@@ -44,12 +44,13 @@ hipError_t h2o_launch_prefill_lse(const h2o_config &cfg, double scale, const voi
 hipError_t h2o_launch_prefill_colsum(const h2o_config &cfg, double scale, const void *Q,
                                      const void *K, int nq, int nk, const float *lse,
                                      float *colsum, hipStream_t st);
-// causal attention over the prompt: V is transposed into `vt` (h2o_attn_vt_bytes
-// bytes), `lse2` receives log2 of every row's normaliser of exp2(scale*log2(e)*<q,k>),
+// causal attention of nq queries (the last nq of nk key positions) over nk keys: V
+// ([nk][d] per head) is transposed into `vt` (h2o_attn_vt_bytes(cfg, nk) bytes),
+// `lse2` receives log2 of every row's normaliser of exp2(scale*log2(e)*<q,k>),
 // `lse_nat` (nullable) the natural-log row log-sum-exp; 16-bit element types only
-size_t h2o_attn_vt_bytes(const h2o_config &cfg, int n);
+size_t h2o_attn_vt_bytes(const h2o_config &cfg, int nk);
 hipError_t h2o_launch_prefill_attention(const h2o_config &cfg, double scale, const void *Q,
-                                        const void *K, const void *V, int n, void *vt,
+                                        const void *K, const void *V, int nq, int nk, void *vt,
                                         float *lse2, float *lse_nat, void *out, hipStream_t st);
 // compression of n candidates per head (entry j: position pos_in[j] or j, score
 // base[j] + score[j] or score[j]) into the cache; t_new = tokens seen afterwards

@@ -1,5 +1,8 @@
 // Causal attention over the prompt on gfx950 (MFMA), with the row statistics
-// that the column-sum pass needs as a by-product.
+// that the column-sum pass needs as a by-product.  The nq queries are the last
+// nq of nk key positions (nq = nk: the whole prompt; nq < nk: a chunk of the
+// prompt attending to cached tokens in front of it): query i sees keys
+// j <= nk - nq + i.
 //
 // The prompt phase of H2O is ordinary full attention over the prompt (App. A,
 // generation commentary: the prompt is processed with the full cache and only
@@ -139,10 +142,11 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__rest
 // ---- attention -------------------------------------------------------------------
 template <int DT, int D>
 __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
-    const char *__restrict__ Qg, const char *__restrict__ Kg, const char *__restrict__ Vtg, int n,
-    int npad, int heads, float c2, float *__restrict__ lse2, float *__restrict__ lse_nat,
+    const char *__restrict__ Qg, const char *__restrict__ Kg, const char *__restrict__ Vtg, int nq,
+    int nk, int npad, int heads, float c2, float *__restrict__ lse2, float *__restrict__ lse_nat,
     char *__restrict__ Og)
 {
+    const int off = nk - nq;               // key position of query 0
     constexpr int ROWB = D * 2;            // bytes per Q/K row
     constexpr int NF = ROWB / 32;          // 16-byte fragments per row per lane half
     constexpr int MB = ABN / 32;           // 32-key blocks per tile
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int grp = wave >> 2;
-    const int nblk = (n + SROWS - 1) / SROWS;
+    const int nblk = (nq + SROWS - 1) / SROWS;
     // a head lives on one XCD (one L2); heaviest (last) row blocks first
     constexpr int HG = 8;
     const int xcd = blockIdx.x & 7, turn = blockIdx.x >> 3;
@@ -178,21 +182,22 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
     if (head >= heads) return;
     const int blk = nblk - 1 - idx / HG;
     const int s0 = blk * SROWS;
-    const char *Qh = Qg + (size_t)head * n * ROWB;
-    const char *Kh = Kg + (size_t)head * n * ROWB;
+    const char *Qh = Qg + (size_t)head * nq * ROWB;
+    const char *Kh = Kg + (size_t)head * nk * ROWB;
     const char *Vth = Vtg + (size_t)head * D * npad * 2;
 
     const int srow = s0 + wave * 32 + l32;           // this lane's query
     uint4 st[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f)
-        st[f] = *reinterpret_cast<const uint4 *>(Qh + (size_t)min(srow, n - 1) * ROWB + (2 * f + half) * 16);
-    if (srow >= n) {
+        st[f] = *reinterpret_cast<const uint4 *>(Qh + (size_t)min(srow, nq - 1) * ROWB + (2 * f + half) * 16);
+    if (srow >= nq) {
 #pragma unroll
         for (int f = 0; f < NF; ++f) st[f] = make_uint4(0, 0, 0, 0);
     }
 
-    const int T = min((n + ABN - 1) / ABN, (s0 + SROWS) / ABN);   // key tiles of this block (>= 1)
+    // key tiles of this block (>= 1): up to the one that holds the last query's own key
+    const int T = min((nk + ABN - 1) / ABN, (off + s0 + SROWS + ABN - 1) / ABN);
 
     // copy plan: instruction c of wave w fills LDS chunks [(c*ANW + w)*64, +64)
     unsigned koff[CPTK], kchunk[CPTK], voff[CPTV];
@@ -209,11 +214,11 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
         const unsigned r = q / CPRV, pos = q % CPRV;
         voff[c] = r * (unsigned)npad * 2u + (pos ^ ((r >> RSHV) & KMASKV)) * 16u;
     }
-    const i32x4 rsrc_k = make_rsrc(Kh, (unsigned)n * ROWB);
+    const i32x4 rsrc_k = make_rsrc(Kh, (unsigned)nk * ROWB);
     const i32x4 rsrc_v = make_rsrc(Vth, (unsigned)D * (unsigned)npad * 2u);
     const unsigned lds_w = __builtin_amdgcn_readfirstlane(
         (unsigned)reinterpret_cast<size_t>(smem) + wave * 1024);
-    const unsigned last_row_off = (unsigned)(n - 1) * ROWB;
+    const unsigned last_row_off = (unsigned)(nk - 1) * ROWB;
     // stage u holds what matrix phase u reads: key tile u and value tile u-1
     // (indices clamped to existing tiles: the first stage's value tile and the
     // last stage's key tile are never read)
@@ -221,10 +226,10 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
         const int kt = min(u, T - 1), vt = min(max(u - 1, 0), T - 1);
         const unsigned t0 = (unsigned)kt * (ABN * ROWB);
         const unsigned base = lds_w + stg * STAGE;
-        if (t0 + ABN * ROWB <= (unsigned)n * ROWB) {
+        if (t0 + ABN * ROWB <= (unsigned)nk * ROWB) {
 #pragma unroll
             for (int c = 0; c < CPTK; ++c) dma16(rsrc_k, koff[c] + kchunk[c], t0, base + c * ANW * 1024);
-        } else {                                       // ragged last tile: rows past n repeat row n-1
+        } else {                                       // ragged last tile: rows past nk repeat row nk-1
 #pragma unroll
             for (int c = 0; c < CPTK; ++c)
                 dma16(rsrc_k, min(t0 + koff[c], last_row_off) + kchunk[c], 0u, base + c * ANW * 1024);
@@ -286,7 +291,7 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
         const int r0 = u * ABN;
         const int w0 = s0 + wave * 32;
         // keys r0.. are visible to this wave only if r0 <= its last query
-        const bool live = !LAST && (!MASKED || r0 <= w0 + 31);
+        const bool live = !LAST && (!MASKED || r0 <= off + w0 + 31);
         f32x16 sacc[MB];
         __builtin_amdgcn_s_setprio(2);
         // Only one wave per SIMD is in its matrix phase, so nothing else hides the
@@ -340,7 +345,7 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int j = r0 + mb * 32 + 16 * (v >> 3) + 8 * half + (v & 7);
-                        if (j > srow) sacc[mb][v] = -INFINITY;
+                        if (j > off + srow) sacc[mb][v] = -INFINITY;
                     }
             }
             float mx = m_run;
@@ -388,7 +393,7 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
         wg_barrier();
     };
     {
-        const int t_diag0 = min(T, s0 / ABN);
+        const int t_diag0 = min(T, (off + s0 + 1) / ABN);   // tiles every query of the block sees in full
         for (int u = 0; u < t_diag0; ++u) step(u, std::false_type{}, std::false_type{});
         for (int u = t_diag0; u < T; ++u) step(u, std::true_type{}, std::false_type{});
         step(T, std::false_type{}, std::true_type{});
@@ -399,9 +404,9 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
     // ---- normalise and store ------------------------------------------------------
     const float l_tot = l_run + other_half(l_run);
     const float inv = 1.0f / l_tot;
-    if (srow < n) {
+    if (srow < nq) {
         using E = Elem<DT>;
-        typename E::T *orow = reinterpret_cast<typename E::T *>(Og) + ((size_t)head * n + srow) * D;
+        typename E::T *orow = reinterpret_cast<typename E::T *>(Og) + ((size_t)head * nq + srow) * D;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -413,21 +418,21 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
             }
         if (half == 0) {
             const float l2 = m_run * c2 + __builtin_amdgcn_logf(l_tot);      // log2 of the row's normaliser
-            lse2[(size_t)head * n + srow] = l2;
-            if (lse_nat) lse_nat[(size_t)head * n + srow] = l2 * 0.69314718055994531f;
+            lse2[(size_t)head * nq + srow] = l2;
+            if (lse_nat) lse_nat[(size_t)head * nq + srow] = l2 * 0.69314718055994531f;
         }
     }
 }
 
 template <int DT, int D>
 hipError_t launch_attn(const h2o_config &cfg, double scale, const void *Q, const void *K,
-                       const void *V, int n, void *vt, float *lse2, float *lse_nat, void *out,
+                       const void *V, int nq, int nk, void *vt, float *lse2, float *lse_nat, void *out,
                        hipStream_t st)
 {
     const int heads = cfg.batch * cfg.heads;
-    const int npad = (n + ABN - 1) / ABN * ABN;
+    const int npad = (nk + ABN - 1) / ABN * ABN;
     hipLaunchKernelGGL((transpose_v_kernel<D>), dim3(heads, npad / ABN), dim3(256), 0, st,
-                       static_cast<const uint16_t *>(V), static_cast<uint16_t *>(vt), n, npad);
+                       static_cast<const uint16_t *>(V), static_cast<uint16_t *>(vt), nk, npad);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     constexpr size_t smem = (size_t)ANS * (ABN * D * 2 + D * ABN * 2);
@@ -439,11 +444,11 @@ hipError_t launch_attn(const h2o_config &cfg, double scale, const void *Q, const
         if (e != hipSuccess) return e;
         raised = true;
     }
-    const int nblk = (n + ANW * 32 - 1) / (ANW * 32);
+    const int nblk = (nq + ANW * 32 - 1) / (ANW * 32);
     const float c2 = (float)(scale * 1.4426950408889634);
     hipLaunchKernelGGL(kern, dim3((unsigned)((heads + 63) / 64) * 64 * nblk), dim3(ANW * 64), smem, st,
                        static_cast<const char *>(Q), static_cast<const char *>(K),
-                       static_cast<const char *>(vt), n, npad, heads, c2, lse2, lse_nat,
+                       static_cast<const char *>(vt), nq, nk, npad, heads, c2, lse2, lse_nat,
                        static_cast<char *>(out));
     return hipGetLastError();
 }
@@ -457,13 +462,14 @@ size_t h2o_attn_vt_bytes(const h2o_config &cfg, int n)
 }
 
 hipError_t h2o_launch_prefill_attention(const h2o_config &cfg, double scale, const void *Q,
-                                        const void *K, const void *V, int n, void *vt,
+                                        const void *K, const void *V, int nq, int nk, void *vt,
                                         float *lse2, float *lse_nat, void *out, hipStream_t st)
 {
     const int d = cfg.head_dim;
+    if (nq < 1 || nq > nk) return hipErrorInvalidValue;
     if (cfg.dtype == H2O_F16)
-        return d == 64 ? launch_attn<H2O_F16, 64>(cfg, scale, Q, K, V, n, vt, lse2, lse_nat, out, st)
-                       : launch_attn<H2O_F16, 128>(cfg, scale, Q, K, V, n, vt, lse2, lse_nat, out, st);
-    return d == 64 ? launch_attn<H2O_BF16, 64>(cfg, scale, Q, K, V, n, vt, lse2, lse_nat, out, st)
-                   : launch_attn<H2O_BF16, 128>(cfg, scale, Q, K, V, n, vt, lse2, lse_nat, out, st);
+        return d == 64 ? launch_attn<H2O_F16, 64>(cfg, scale, Q, K, V, nq, nk, vt, lse2, lse_nat, out, st)
+                       : launch_attn<H2O_F16, 128>(cfg, scale, Q, K, V, nq, nk, vt, lse2, lse_nat, out, st);
+    return d == 64 ? launch_attn<H2O_BF16, 64>(cfg, scale, Q, K, V, nq, nk, vt, lse2, lse_nat, out, st)
+                   : launch_attn<H2O_BF16, 128>(cfg, scale, Q, K, V, nq, nk, vt, lse2, lse_nat, out, st);
 }

@@ -70,6 +70,10 @@ def test_size_queries_and_validation(hb):
     ncat = 410 + 512
     assert hb.h2o_prefill_chunk_workspace_bytes(ok, 512) == \
         2 * 16 * 32 * ncat * 128 * 2 + 3 * 16 * 32 * ncat * 4 + 16 * 32 * 512 * 4
+    # with the attention output: + V of cache + chunk transposed, padded to whole 64-key tiles
+    assert hb.h2o_prefill_chunk_workspace_bytes(ok, 512, True) == \
+        hb.h2o_prefill_chunk_workspace_bytes(ok, 512) + 16 * 32 * 128 * 960 * 2
+    assert hb.h2o_prefill_chunk_workspace_bytes(hb.make_config(1, 1, 128, 4, 4, hb.H2O_F32), 8, True) == 0
     assert hb.h2o_prefill_chunk_workspace_bytes(ok, 0) == 0
     assert hb.h2o_prefill_chunk_workspace_bytes(ok, hb.H2O_MAX_PROMPT - 409) == 0
     assert hb.h2o_prefill_chunk_workspace_bytes(bad[0], 8) == 0
@@ -102,7 +106,7 @@ def test_error_codes_without_device(hb):
                                      0x1000, None, None) == hb.H2O_EUNSUPPORTED
     assert lib.h2o_prefill_attention_scores(None, 0x1000, 0x1000, 0x1000, 8, 0x1000, 1 << 20, 0x1000,
                                             None, None) == hb.H2O_EINVAL
-    assert lib.h2o_prefill_chunk(None, 0x1000, 0x1000, 0x1000, 8, 0x1000, 1 << 20, None) == hb.H2O_EINVAL
+    assert lib.h2o_prefill_chunk(None, 0x1000, 0x1000, 0x1000, 8, 0x1000, 1 << 20, None, None) == hb.H2O_EINVAL
     lib.h2o_cache_destroy(None)
     assert hb.h2o_status_str(0) == "ok"
     assert "unsupported" in hb.h2o_status_str(hb.H2O_EUNSUPPORTED)

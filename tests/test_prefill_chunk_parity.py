@@ -6,6 +6,7 @@ import torch
 
 from oracle.h2o_oracle import OracleHead, map_heads
 from tests import parity
+from tests.test_prefill_attention_parity import check_rows
 from tests.test_prefill_parity import COLSUM_ATOL, COLSUM_RTOL, SELECT_RTOL
 
 pytestmark = pytest.mark.gpu
@@ -13,7 +14,7 @@ pytestmark = pytest.mark.gpu
 torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 
-def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, decode_steps=0):
+def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, decode_steps=0, attn=False):
     """Feeds the prompt chunk by chunk to the device and to the oracle.  After
     every chunk: same kept positions (a difference is accepted only between tokens
     whose oracle rank values lie within SELECT_RTOL of each other, i.e. at the
@@ -25,8 +26,9 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
     k = heavy + recent
     Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, sigma, dev, seed)
     cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, device=dev, rank=rank)
-    need = hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, max(chunks))
+    need = hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, max(chunks), attn)
     assert need > 0
+    out_max = [0.0, 0.0]
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     heads = [(b, h) for b in range(B) for h in range(Hh)]
     scale = parity.oracle_scale(d)
@@ -38,20 +40,29 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
     t0 = 0
     for m in chunks:
         q, kk, v = (x[:, :, t0:t0 + m].contiguous() for x in (Q, K, V))
-        hb.h2o_prefill_chunk(cache.handle, q, kk, v, m, ws, need)
+        out = torch.empty_like(q) if attn else None
+        hb.h2o_prefill_chunk(cache.handle, q, kk, v, m, ws, need, out)
         pos, acc = cache.snapshot()
         torch.cuda.synchronize()
+        out = out.cpu().double().numpy() if attn else None
+        ref_attn = {}
         pos, acc = pos.cpu().numpy(), acc.cpu().numpy()
         t1 = t0 + m
         assert cache.tokens_seen == t1
 
         def one(bh):
             b, h = bh
-            oracles[bh].prefill_chunk(parity.host64(Qc[b, h, t0:t1]), parity.host64(Kc[b, h, t0:t1]),
-                                      parity.host64(Vc[b, h, t0:t1]))
+            _, ref_attn[bh] = oracles[bh].prefill_chunk(
+                parity.host64(Qc[b, h, t0:t1]), parity.host64(Kc[b, h, t0:t1]),
+                parity.host64(Vc[b, h, t0:t1]), want_attn=attn)
         map_heads(one, sorted(alive))
         for (b, h) in sorted(alive):
             o = oracles[(b, h)]
+            if attn:
+                # the chunk's attention output was formed on the cache as it was before the call
+                l2, li = check_rows(out[b, h], ref_attn[(b, h)], dtype,
+                                    "head (%d, %d) chunk ending at %d" % (b, h, t1))
+                out_max[0], out_max[1] = max(out_max[0], l2), max(out_max[1], li)
             rp, rs = o.resident()
             gp = pos[b, h][pos[b, h] >= 0]
             assert len(gp) == len(rp) == min(t1, k)
@@ -73,9 +84,10 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
             assert np.all(np.abs(got - ref) <= COLSUM_RTOL * np.abs(ref) + COLSUM_ATOL), \
                 "scores differ after chunk ending at %d" % t1
         t0 = t1
-    print("\n[chunked prompt] B=%d Hh=%d d=%d chunks=%s H=%d R=%d %s rank=%d: heads %d, dropped at threshold %d"
+    print("\n[chunked prompt] B=%d Hh=%d d=%d chunks=%s H=%d R=%d %s rank=%d: heads %d, dropped at threshold %d%s"
           % (B, Hh, d, chunks if len(chunks) < 8 else "%dx%d" % (len(chunks), chunks[0]), heavy, recent,
-             str(dtype).split(".")[-1], rank, len(heads), len(heads) - len(alive)), flush=True)
+             str(dtype).split(".")[-1], rank, len(heads), len(heads) - len(alive),
+             ", attention rows l2 %.2e linf %.2e" % tuple(out_max) if attn else ""), flush=True)
     assert len(alive) >= 0.9 * len(heads)
     if decode_steps:
         qs, ks, vs = synth.make_steps(B, Hh, d, decode_steps, dtype, sigma, dev, seed)
@@ -111,6 +123,31 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
 ])
 def test_chunked_prompt(dt, d, chunks, heavy, recent):
     chunk_case(2, 2, d, chunks, heavy, recent, torch_dt[dt], 1.0, 51)
+
+
+@pytest.mark.parametrize("dt,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("bf16", 64)])
+@pytest.mark.parametrize("chunks,heavy,recent", [
+    ([300, 300, 300], 64, 64),
+    ([40] * 6, 100, 60),
+    ([1, 255, 256, 257, 31], 50, 50),
+    ([700], 64, 64),
+    ([1000, 600], 205, 205),
+])
+def test_chunked_prompt_with_attention_output(dt, d, chunks, heavy, recent):
+    chunk_case(2, 2, d, chunks, heavy, recent, torch_dt[dt], 1.0, 58, attn=True)
+
+
+def test_chunked_prompt_attention_output_refused_for_binary32():
+    from paper_2306_14048_amd import binding as hb, synth
+    dev = torch.device("cuda:0")
+    Q, K, V = synth.make_prompt(1, 1, 32, 64, torch.float32, 1.0, dev, 3)
+    cache = hb.H2OCache(1, 1, 64, 8, 8, torch.float32, device=dev)
+    with pytest.raises(hb.H2OError) as ei:
+        cache.prefill_chunk(Q, K, V, out=torch.empty_like(Q))
+    assert ei.value.status == hb.H2O_EUNSUPPORTED
+    cache.prefill_chunk(Q, K, V)
+    assert cache.tokens_seen == 32
+    cache.close()
 
 
 def test_chunked_prompt_heavy_only_and_window_only():
