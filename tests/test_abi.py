@@ -34,6 +34,20 @@ def test_header_and_library_agree(hb):
     assert sorted(hb.EXPORTS) == names, "python binding and header list different entry points"
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_h2o.c"
+    src.write_text('#include "h2o.h"\n'
+                   'int main(void) { h2o_config c = {0}; c.kv_bits = 4; '
+                   'int (*step)(h2o_cache *, const void *, const void *, const void *, void *, void *) = h2o_decode_step; '
+                   'return (int)sizeof(c) + H2O_Q4_ROW_BYTES(128) + (step == 0); }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(root, "include"), str(src)])
+
+
 def test_size_queries_and_validation(hb):
     ok = hb.make_config(16, 32, 128, 205, 205, hb.H2O_F16)
     # K | V | acc | pos, each padded to 256 bytes

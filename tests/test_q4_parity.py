@@ -54,10 +54,14 @@ def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="s
             for (b, h) in heads:
                 score[b, h] = torch.from_numpy(cols[(b, h)].astype(np.float32))
             cache.prefill_select(K, V, score.to(dev))
+        elif prompt == "attention":
+            need = hb.h2o_prefill_attention_workspace_bytes(cache.cfg, n)
+            ws = torch.empty(need, dtype=torch.uint8, device=dev)
+            hb.h2o_prefill_attention_scores(cache.handle, Q, K, V, n, ws, need, torch.empty_like(Q))
         else:
             cache.prefill_scores(Q, K, V)
         torch.cuda.synchronize()
-        if prompt == "scores":
+        if prompt != "select":
             # the device's own column sums: a token at the selection threshold may change sides
             pos = cache.views()[3].cpu().numpy()
             same = [bh for bh in heads
@@ -96,7 +100,7 @@ def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="s
              total.max_score_rel, rows), flush=True)
     assert total.excused <= max(1, total.head_steps // 1000)
     # scores seeded by the device's own column sums carry that pass's tolerance
-    assert total.max_score_rel <= (1e-4 if prompt == "scores" else 1e-6)
+    assert total.max_score_rel <= (1e-6 if prompt == "select" else 1e-4)
     cache.close()
     return total
 
@@ -140,6 +144,10 @@ def test_q4_decode_averaged_ranking():
 
 def test_q4_end_to_end_with_device_prompt_scoring():
     q4_case(2, 4, 128, 1024, 32, 103, 102, torch.float16, 1.0, 68, prompt="scores")
+
+
+def test_q4_end_to_end_with_attention_based_prompt_phase():
+    q4_case(2, 4, 128, 1024, 16, 103, 102, torch.bfloat16, 1.0, 70, prompt="attention")
 
 
 def test_q4_heavy_tailed_keys():
