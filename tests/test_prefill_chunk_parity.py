@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 
-def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, decode_steps=0, attn=False):
+def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, decode_steps=0, attn=False,
+               sample=None):
     """Feeds the prompt chunk by chunk to the device and to the oracle.  After
     every chunk: same kept positions (a difference is accepted only between tokens
     whose oracle rank values lie within SELECT_RTOL of each other, i.e. at the
@@ -31,6 +32,9 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
     out_max = [0.0, 0.0]
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     heads = [(b, h) for b in range(B) for h in range(Hh)]
+    if sample is not None:                       # full-size runs: the oracle follows a sample of the heads
+        rng = np.random.default_rng(seed)
+        heads = [heads[i] for i in sorted(rng.choice(len(heads), size=sample, replace=False))]
     scale = parity.oracle_scale(d)
     oracles = {bh: OracleHead(d, heavy, recent, scale, score_f32=True, cap=n + decode_steps, policy=rank)
                for bh in heads}
@@ -168,6 +172,12 @@ def test_chunked_prompt_large_budget_and_chunks():
     2048 + 2048 budget fed in 2048-token chunks."""
     chunk_case(1, 4, 128, [1024] * 4, 205, 205, torch.float16, 1.0, 56)
     chunk_case(1, 2, 128, [2048] * 3, 2048, 2048, torch.bfloat16, 1.0, 57)
+
+
+def test_chunked_prompt_full_size_prompt_workload_sampled():
+    """The prompt-only workload's shape (batch 4, 32 heads, 4096 tokens, bf16, 20 % budget) in
+    1024-token chunks with attention output, 8 sampled heads."""
+    chunk_case(4, 32, 128, [1024] * 4, 410, 409, torch.bfloat16, 1.0, 59, attn=True, sample=8)
 
 
 def test_chunk_refused_after_an_eviction_and_allowed_after_reset():

@@ -35,7 +35,7 @@ def check_stored_rows(hb, cache, oracles, d):
     return rows
 
 
-def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="select"):
+def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="select", sample=None):
     """Prompt phase, then T generation steps on a 4-bit cache.  prompt = "select":
     the device compresses on the ORACLE's binary32 scores (bit-exact index work,
     both sides start from the same set); "scores": the device's own prompt scoring."""
@@ -43,6 +43,10 @@ def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="s
     dev = torch.device("cuda:0")
     k = heavy + recent
     heads = [(b, h) for b in range(B) for h in range(Hh)]
+    if sample is not None:                       # full-size runs: the oracle follows a sample of the heads
+        assert prompt != "select"
+        rng = np.random.default_rng(seed)
+        heads = [heads[i] for i in sorted(rng.choice(len(heads), size=sample, replace=False))]
     scale = parity.oracle_scale(d)
     cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, device=dev, rank=rank, kv_bits=4)
     if n > 0:
@@ -148,6 +152,12 @@ def test_q4_end_to_end_with_device_prompt_scoring():
 
 def test_q4_end_to_end_with_attention_based_prompt_phase():
     q4_case(2, 4, 128, 1024, 16, 103, 102, torch.bfloat16, 1.0, 70, prompt="attention")
+
+
+def test_q4_full_size_layer_workload_sampled():
+    """The OPT-6.7B-shaped layer (batch 16, 32 heads, prompt 2048, budget 205 + 205, f16) on a 4-bit
+    cache: device prompt scoring, 64 generation steps, 12 sampled heads."""
+    q4_case(16, 32, 128, 2048, 64, 205, 205, torch.float16, 1.0, 71, prompt="scores", sample=12)
 
 
 def test_q4_heavy_tailed_keys():
