@@ -313,12 +313,12 @@ template <int ROWB>
 __global__ __launch_bounds__(256) void concat_kernel(
     const char *__restrict__ Kc, const char *__restrict__ Vc, const float *__restrict__ acc_g,
     const int32_t *__restrict__ pos_g, const char *__restrict__ Kn, const char *__restrict__ Vn,
-    int k, int n_occ, int m, int t, char *__restrict__ Kcat, char *__restrict__ Vcat,
-    float *__restrict__ base, int32_t *__restrict__ pos_cat)
+    int k, int n_occ, int m, int t, int blocks_per_head, char *__restrict__ Kcat,
+    char *__restrict__ Vcat, float *__restrict__ base, int32_t *__restrict__ pos_cat)
 {
     constexpr int LPR = ROWB / 16;
-    const int head = blockIdx.y, ncat = n_occ + m;
-    const int row = blockIdx.x * (256 / LPR) + threadIdx.x / LPR, li = threadIdx.x % LPR;
+    const int head = blockIdx.x / blocks_per_head, ncat = n_occ + m;
+    const int row = (blockIdx.x % blocks_per_head) * (256 / LPR) + threadIdx.x / LPR, li = threadIdx.x % LPR;
     if (row >= ncat) return;
     const bool cached = row < n_occ;
     const char *ks = cached ? Kc + ((size_t)head * k + row) * ROWB : Kn + ((size_t)head * m + (row - n_occ)) * ROWB;
@@ -338,12 +338,16 @@ hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn,
     const int heads = c.cfg.batch * c.cfg.heads;
     const int rowb = c.cfg.head_dim * c.esize;
     const int ncat = n_occ + m;
-    if (heads > 65535) return hipErrorInvalidValue;
+    // one-dimensional grid: heads x blocks per head (at most 2^24 x 4352 / 8 < 2^34 is refused below)
 #define H2O_CC(RB)                                                                               \
-    hipLaunchKernelGGL((concat_kernel<RB>), dim3((ncat + 256 / (RB / 16) - 1) / (256 / (RB / 16)), heads), \
-                       dim3(256), 0, st, c.K, c.V, c.acc, c.pos, static_cast<const char *>(Kn),  \
-                       static_cast<const char *>(Vn), c.k, n_occ, m, c.t, static_cast<char *>(Kcat), \
-                       static_cast<char *>(Vcat), base, pos_cat)
+    do {                                                                                         \
+        const int bph = (ncat + 256 / (RB / 16) - 1) / (256 / (RB / 16));                        \
+        if ((long long)heads * bph > 0x7fffffffLL) return hipErrorInvalidValue;                  \
+        hipLaunchKernelGGL((concat_kernel<RB>), dim3((unsigned)(heads * bph)), dim3(256), 0, st, \
+                           c.K, c.V, c.acc, c.pos, static_cast<const char *>(Kn),                \
+                           static_cast<const char *>(Vn), c.k, n_occ, m, c.t, bph,               \
+                           static_cast<char *>(Kcat), static_cast<char *>(Vcat), base, pos_cat); \
+    } while (0)
     switch (rowb) {
     case 128: H2O_CC(128); break;
     case 256: H2O_CC(256); break;
