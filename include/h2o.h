@@ -175,8 +175,8 @@ int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K,
 
 /* Device bytes of scratch h2o_prefill_chunk needs for chunks of up to m tokens
  * (cache + chunk as one candidate list: K and V rows, old scores, positions,
- * column sums, row statistics; with_output != 0: also the transposed V the
- * attention output needs).  Returns 0 for invalid arguments, when heavy + recent
+ * column sums, row statistics, slot order; with_output != 0: also the transposed
+ * V the attention output needs).  Returns 0 for invalid arguments, when heavy + recent
  * + m exceeds H2O_MAX_PROMPT, and for with_output on a binary32 configuration. */
 size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m, int32_t with_output);
 
@@ -198,10 +198,11 @@ size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m, int32
  *             output of the chunk's tokens (sum over cached and chunk tokens of
  *             probability times value), which makes the call a layer's complete
  *             attention for the chunk; 16-bit element types only
- * The cached tokens must sit in ascending position order, which holds after
- * h2o_cache_init / _reset / h2o_prefill_* and until a generation step evicts.
- * Then t becomes t + m.  Errors: EINVAL, EUNSUPPORTED, ENOMEM, ESTATE (slots no
- * longer in position order), EHIP.
+ * May follow generation steps (a further prompt after some generated tokens):
+ * the cached tokens are taken in position order whichever slots they sit in;
+ * afterwards they sit in slots in ascending position order.
+ * Then t becomes t + m.  Errors: EINVAL, EUNSUPPORTED (4-bit cache; out on a
+ * binary32 configuration), ENOMEM, EHIP.
  */
 int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void *V,
                       int32_t m, void *workspace, size_t ws_bytes, void *out, void *hip_stream);

@@ -205,9 +205,11 @@ size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m, int32
     const size_t heads = (size_t)cfg->batch * cfg->heads, ncat = k + m;
     const size_t rows = align_up(heads * ncat * cfg->head_dim * h2o_esize(cfg->dtype), 256);
     const size_t vec = align_up(heads * ncat * sizeof(float), 256);
-    // K and V of cache + chunk, old scores, positions, column sums, row statistics
-    // (+ the transposed V of cache + chunk when the attention output is wanted)
+    // K and V of cache + chunk, old scores, positions, column sums, row statistics,
+    // the slots in position order (+ the transposed V of cache + chunk when the
+    // attention output is wanted)
     return 2 * rows + 3 * vec + align_up(heads * (size_t)m * sizeof(float), 256) +
+           align_up(heads * k * sizeof(int32_t), 256) +
            (with_output ? align_up(h2o_attn_vt_bytes(*cfg, (int)ncat), 256) : 0);
 }
 
@@ -219,7 +221,6 @@ int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void
         return H2O_EINVAL;
     if (cache->cfg.kv_bits != 0) return H2O_EUNSUPPORTED;   // cached rows would have to be dequantised
     if (out && cache->cfg.dtype == H2O_F32) return H2O_EUNSUPPORTED;
-    if (!cache->sorted) return H2O_ESTATE;
     const h2o_config &cfg = cache->cfg;
     const int occ = cache->t < cache->k ? cache->t : cache->k;
     if ((int64_t)cache->k + m > H2O_MAX_PROMPT || (int64_t)cache->t + m >= 0x7ffffff0) return H2O_EUNSUPPORTED;
@@ -234,10 +235,14 @@ int h2o_prefill_chunk(h2o_cache *cache, const void *Q, const void *K, const void
     int32_t *pos_cat = reinterpret_cast<int32_t *>(ws + 2 * rows + vec);
     float *colsum = reinterpret_cast<float *>(ws + 2 * rows + 2 * vec);
     float *lse = reinterpret_cast<float *>(ws + 2 * rows + 3 * vec);
-    char *vt = ws + 2 * rows + 3 * vec + align_up(heads * (size_t)m * sizeof(float), 256);
+    int32_t *order = reinterpret_cast<int32_t *>(ws + 2 * rows + 3 * vec +
+                                                 align_up(heads * (size_t)m * sizeof(float), 256));
+    char *vt = reinterpret_cast<char *>(order) + align_up(heads * (size_t)cache->k * sizeof(int32_t), 256);
     const int ncat = occ + m;
     const double scale = h2o_scale_of(cfg);
-    hipError_t e = h2o_launch_concat(*cache, K, V, m, occ, Kcat, Vcat, base, pos_cat, st);
+    // after generation steps have evicted, the slots are first put in position order
+    hipError_t e = h2o_launch_concat(*cache, K, V, m, occ, cache->sorted ? nullptr : order, Kcat, Vcat,
+                                     base, pos_cat, st);
     if (e != hipSuccess) return H2O_EHIP;
     // row statistics: a by-product of the attention output when that is wanted
     e = out ? h2o_launch_prefill_attention(cfg, scale, Q, Kcat, Vcat, m, ncat, vt, lse, nullptr, out, st)

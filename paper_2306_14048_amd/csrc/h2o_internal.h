@@ -57,9 +57,12 @@ hipError_t h2o_launch_prefill_attention(const h2o_config &cfg, double scale, con
 hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const void *V,
                                     const float *score, const float *base, const int32_t *pos_in,
                                     int n, int t_new, hipStream_t st);
-// the n_occ cached tokens followed by the m chunk tokens as one candidate list
+// the n_occ cached tokens in position order followed by the m chunk tokens as one
+// candidate list; `order` (heads * k ints of scratch) is needed when the slots are
+// not in position order, nullptr when they are
 hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn, int m, int n_occ,
-                             void *Kcat, void *Vcat, float *base, int32_t *pos_cat, hipStream_t st);
+                             int32_t *order, void *Kcat, void *Vcat, float *base, int32_t *pos_cat,
+                             hipStream_t st);
 
 // ---- element types ----------------------------------------------------------
 // Raw storage views: f32 -> float, f16 -> _Float16, bf16 -> uint16_t bit pattern.

@@ -309,42 +309,71 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
 // position order) followed by the m tokens of the chunk as one sequence of
 // ncat = n_occ + m candidates: their K/V rows, the scores they already have
 // (zero for the chunk) and their positions are laid out contiguously per head.
+// `order` (nullable): order[head][r] = the slot that holds the r-th cached token in
+// position order; nullptr = the slots already are in that order.
 template <int ROWB>
 __global__ __launch_bounds__(256) void concat_kernel(
     const char *__restrict__ Kc, const char *__restrict__ Vc, const float *__restrict__ acc_g,
-    const int32_t *__restrict__ pos_g, const char *__restrict__ Kn, const char *__restrict__ Vn,
-    int k, int n_occ, int m, int t, int blocks_per_head, char *__restrict__ Kcat,
-    char *__restrict__ Vcat, float *__restrict__ base, int32_t *__restrict__ pos_cat)
+    const int32_t *__restrict__ pos_g, const int32_t *__restrict__ order, const char *__restrict__ Kn,
+    const char *__restrict__ Vn, int k, int n_occ, int m, int t, int blocks_per_head,
+    char *__restrict__ Kcat, char *__restrict__ Vcat, float *__restrict__ base,
+    int32_t *__restrict__ pos_cat)
 {
     constexpr int LPR = ROWB / 16;
     const int head = blockIdx.x / blocks_per_head, ncat = n_occ + m;
     const int row = (blockIdx.x % blocks_per_head) * (256 / LPR) + threadIdx.x / LPR, li = threadIdx.x % LPR;
     if (row >= ncat) return;
     const bool cached = row < n_occ;
-    const char *ks = cached ? Kc + ((size_t)head * k + row) * ROWB : Kn + ((size_t)head * m + (row - n_occ)) * ROWB;
-    const char *vs = cached ? Vc + ((size_t)head * k + row) * ROWB : Vn + ((size_t)head * m + (row - n_occ)) * ROWB;
+    const int slot = cached ? (order ? order[(size_t)head * k + row] : row) : 0;
+    const char *ks = cached ? Kc + ((size_t)head * k + slot) * ROWB : Kn + ((size_t)head * m + (row - n_occ)) * ROWB;
+    const char *vs = cached ? Vc + ((size_t)head * k + slot) * ROWB : Vn + ((size_t)head * m + (row - n_occ)) * ROWB;
     const size_t o = ((size_t)head * ncat + row) * ROWB + li * 16;
     *reinterpret_cast<uint4 *>(Kcat + o) = *reinterpret_cast<const uint4 *>(ks + li * 16);
     *reinterpret_cast<uint4 *>(Vcat + o) = *reinterpret_cast<const uint4 *>(vs + li * 16);
     if (li == 0) {
-        base[(size_t)head * ncat + row] = cached ? acc_g[(size_t)head * k + row] : 0.f;
-        pos_cat[(size_t)head * ncat + row] = cached ? pos_g[(size_t)head * k + row] : t + (row - n_occ);
+        base[(size_t)head * ncat + row] = cached ? acc_g[(size_t)head * k + slot] : 0.f;
+        pos_cat[(size_t)head * ncat + row] = cached ? pos_g[(size_t)head * k + slot] : t + (row - n_occ);
+    }
+}
+
+// Generation steps overwrite evicted slots in place, so slot order stops following
+// position order.  order[head][r] = slot of the r-th smallest position among the
+// n_occ occupied slots (the first n_occ), by counting: positions are distinct.
+__global__ __launch_bounds__(256) void order_slots_kernel(const int32_t *__restrict__ pos_g, int k,
+                                                          int n_occ, int32_t *__restrict__ order)
+{
+    extern __shared__ int32_t pos_l[];
+    const size_t hoff = (size_t)blockIdx.x * k;
+    for (int s = threadIdx.x; s < n_occ; s += 256) pos_l[s] = pos_g[hoff + s];
+    __syncthreads();
+    for (int s = threadIdx.x; s < n_occ; s += 256) {
+        const int p = pos_l[s];
+        int rank = 0;
+        for (int j = 0; j < n_occ; ++j) rank += pos_l[j] < p;
+        order[hoff + rank] = s;
     }
 }
 
 hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn, int m, int n_occ,
-                             void *Kcat, void *Vcat, float *base, int32_t *pos_cat, hipStream_t st)
+                             int32_t *order, void *Kcat, void *Vcat, float *base, int32_t *pos_cat,
+                             hipStream_t st)
 {
     const int heads = c.cfg.batch * c.cfg.heads;
     const int rowb = c.cfg.head_dim * c.esize;
     const int ncat = n_occ + m;
+    if (order && n_occ > 0) {
+        hipLaunchKernelGGL(order_slots_kernel, dim3(heads), dim3(256), (size_t)n_occ * sizeof(int32_t), st,
+                           c.pos, c.k, n_occ, order);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     // one-dimensional grid: heads x blocks per head (at most 2^24 x 4352 / 8 < 2^34 is refused below)
 #define H2O_CC(RB)                                                                               \
     do {                                                                                         \
         const int bph = (ncat + 256 / (RB / 16) - 1) / (256 / (RB / 16));                        \
         if ((long long)heads * bph > 0x7fffffffLL) return hipErrorInvalidValue;                  \
         hipLaunchKernelGGL((concat_kernel<RB>), dim3((unsigned)(heads * bph)), dim3(256), 0, st, \
-                           c.K, c.V, c.acc, c.pos, static_cast<const char *>(Kn),                \
+                           c.K, c.V, c.acc, c.pos, order, static_cast<const char *>(Kn),         \
                            static_cast<const char *>(Vn), c.k, n_occ, m, c.t, bph,               \
                            static_cast<char *>(Kcat), static_cast<char *>(Vcat), base, pos_cat); \
     } while (0)

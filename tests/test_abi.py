@@ -83,7 +83,7 @@ def test_size_queries_and_validation(hb):
     # cache + chunk as one candidate list: K, V rows; old scores, positions, column sums; row statistics
     ncat = 410 + 512
     assert hb.h2o_prefill_chunk_workspace_bytes(ok, 512) == \
-        2 * 16 * 32 * ncat * 128 * 2 + 3 * 16 * 32 * ncat * 4 + 16 * 32 * 512 * 4
+        2 * 16 * 32 * ncat * 128 * 2 + 3 * 16 * 32 * ncat * 4 + 16 * 32 * 512 * 4 + 16 * 32 * 410 * 4
     # with the attention output: + V of cache + chunk transposed, padded to whole 64-key tiles
     assert hb.h2o_prefill_chunk_workspace_bytes(ok, 512, True) == \
         hb.h2o_prefill_chunk_workspace_bytes(ok, 512) + 16 * 32 * 128 * 960 * 2

@@ -16,18 +16,25 @@ torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, decode_steps=0, attn=False,
                sample=None):
-    """Feeds the prompt chunk by chunk to the device and to the oracle.  After
-    every chunk: same kept positions (a difference is accepted only between tokens
-    whose oracle rank values lie within SELECT_RTOL of each other, i.e. at the
-    selection threshold; that head is then no longer compared), scores within the
-    column-sum tolerance.  Optionally continues with generation steps."""
+    """Feeds the prompt chunk by chunk to the device and to the oracle.  `chunks`
+    lists chunk lengths; an entry ("steps", T) stands for T generation steps at
+    that point (a further prompt may follow generated tokens), and `decode_steps`
+    appends one such entry.  After every chunk: same kept positions (a difference
+    is accepted only between tokens whose oracle rank values lie within SELECT_RTOL
+    of each other, i.e. at the selection threshold; that head is then no longer
+    compared), scores within the column-sum tolerance, attention rows if asked for.
+    After every generation step: outputs and kept sets."""
     from paper_2306_14048_amd import binding as hb, synth
     dev = torch.device("cuda:0")
-    n = sum(chunks)
+    schedule = list(chunks) + ([("steps", decode_steps)] if decode_steps else [])
+    sizes = [x for x in schedule if isinstance(x, int)]
+    n = sum(sizes)
+    T = sum(x[1] for x in schedule if not isinstance(x, int))
     k = heavy + recent
     Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, sigma, dev, seed)
+    qs, ks, vs = synth.make_steps(B, Hh, d, T, dtype, sigma, dev, seed)
     cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, device=dev, rank=rank)
-    need = hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, max(chunks), attn)
+    need = hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, max(sizes), attn)
     assert need > 0
     out_max = [0.0, 0.0]
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
@@ -36,14 +43,40 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
         rng = np.random.default_rng(seed)
         heads = [heads[i] for i in sorted(rng.choice(len(heads), size=sample, replace=False))]
     scale = parity.oracle_scale(d)
-    oracles = {bh: OracleHead(d, heavy, recent, scale, score_f32=True, cap=n + decode_steps, policy=rank)
+    oracles = {bh: OracleHead(d, heavy, recent, scale, score_f32=True, cap=n + T, policy=rank)
                for bh in heads}
     Qc, Kc, Vc = Q.cpu(), K.cpu(), V.cpu()
     alive = set(heads)
     flips = 0
-    t0 = 0
-    for m in chunks:
-        q, kk, v = (x[:, :, t0:t0 + m].contiguous() for x in (Q, K, V))
+    tol = parity.OUT_TOL[dtype] + parity.OUT_STORE_SLACK[dtype]
+    c0 = 0                  # prompt tokens consumed
+    s0 = 0                  # generation steps consumed
+    t = 0                   # tokens seen
+    for item in schedule:
+        if not isinstance(item, int):
+            out = torch.empty((B, Hh, d), dtype=dtype, device=dev)
+            for s in range(s0, s0 + item[1]):
+                cache.decode_step(qs[s], ks[s], vs[s], out)
+                pos, _ = cache.snapshot()
+                torch.cuda.synchronize()
+                o_gpu, pos = out.cpu().double().numpy(), pos.cpu().numpy()
+                for (b, h) in sorted(alive):
+                    o = oracles[(b, h)]
+                    r = o.decode(parity.host64(qs[s, b, h]), parity.host64(ks[s, b, h]),
+                                 parity.host64(vs[s, b, h]))
+                    err = np.linalg.norm(o_gpu[b, h] - r.out) / max(np.linalg.norm(r.out), 1e-300)
+                    assert err <= tol, "output of a step after chunked prompt off by %.2e" % err
+                    gp = set(pos[b, h][pos[b, h] >= 0].tolist())
+                    if gp != set(o.resident()[0].tolist()):
+                        # scores carry the column-sum tolerance: a near-tie may break the other way
+                        assert np.isfinite(r.second) and (r.second - r.lowest) <= SELECT_RTOL * abs(r.second)
+                        alive.discard((b, h))
+            s0 += item[1]
+            t += item[1]
+            assert cache.tokens_seen == t
+            continue
+        m = item
+        q, kk, v = (x[:, :, c0:c0 + m].contiguous() for x in (Q, K, V))
         out = torch.empty_like(q) if attn else None
         hb.h2o_prefill_chunk(cache.handle, q, kk, v, m, ws, need, out)
         pos, acc = cache.snapshot()
@@ -51,14 +84,14 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
         out = out.cpu().double().numpy() if attn else None
         ref_attn = {}
         pos, acc = pos.cpu().numpy(), acc.cpu().numpy()
-        t1 = t0 + m
+        t1 = t + m
         assert cache.tokens_seen == t1
 
         def one(bh):
             b, h = bh
             _, ref_attn[bh] = oracles[bh].prefill_chunk(
-                parity.host64(Qc[b, h, t0:t1]), parity.host64(Kc[b, h, t0:t1]),
-                parity.host64(Vc[b, h, t0:t1]), want_attn=attn)
+                parity.host64(Qc[b, h, c0:c0 + m]), parity.host64(Kc[b, h, c0:c0 + m]),
+                parity.host64(Vc[b, h, c0:c0 + m]), want_attn=attn)
         map_heads(one, sorted(alive))
         for (b, h) in sorted(alive):
             o = oracles[(b, h)]
@@ -87,32 +120,14 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
             ref = np.array([lut[int(j)] for j in gp])
             assert np.all(np.abs(got - ref) <= COLSUM_RTOL * np.abs(ref) + COLSUM_ATOL), \
                 "scores differ after chunk ending at %d" % t1
-        t0 = t1
-    print("\n[chunked prompt] B=%d Hh=%d d=%d chunks=%s H=%d R=%d %s rank=%d: heads %d, dropped at threshold %d%s"
-          % (B, Hh, d, chunks if len(chunks) < 8 else "%dx%d" % (len(chunks), chunks[0]), heavy, recent,
+        c0 += m
+        t = t1
+    shown = [x if isinstance(x, int) else "%d steps" % x[1] for x in schedule]
+    print("\n[chunked prompt] B=%d Hh=%d d=%d schedule=%s H=%d R=%d %s rank=%d: heads %d, dropped at threshold %d%s"
+          % (B, Hh, d, shown if len(shown) < 8 else "%dx%s" % (len(shown), shown[0]), heavy, recent,
              str(dtype).split(".")[-1], rank, len(heads), len(heads) - len(alive),
              ", attention rows l2 %.2e linf %.2e" % tuple(out_max) if attn else ""), flush=True)
     assert len(alive) >= 0.9 * len(heads)
-    if decode_steps:
-        qs, ks, vs = synth.make_steps(B, Hh, d, decode_steps, dtype, sigma, dev, seed)
-        out = torch.empty((B, Hh, d), dtype=dtype, device=dev)
-        tol = parity.OUT_TOL[dtype] + parity.OUT_STORE_SLACK[dtype]
-        for s in range(decode_steps):
-            cache.decode_step(qs[s], ks[s], vs[s], out)
-            pos, _ = cache.snapshot()
-            torch.cuda.synchronize()
-            o_gpu, pos = out.cpu().double().numpy(), pos.cpu().numpy()
-            for (b, h) in sorted(alive):
-                o = oracles[(b, h)]
-                r = o.decode(parity.host64(qs[s, b, h]), parity.host64(ks[s, b, h]), parity.host64(vs[s, b, h]))
-                err = np.linalg.norm(o_gpu[b, h] - r.out) / max(np.linalg.norm(r.out), 1e-300)
-                assert err <= tol, "output after chunked prompt off by %.2e" % err
-                gp = set(pos[b, h][pos[b, h] >= 0].tolist())
-                if gp != set(o.resident()[0].tolist()):
-                    # scores carry the column-sum tolerance: a near-tie may break the other way
-                    assert np.isfinite(r.second) and (r.second - r.lowest) <= SELECT_RTOL * abs(r.second)
-                    alive.discard((b, h))
-        assert len(alive) >= 0.9 * len(heads)
     cache.close()
     return flips
 
@@ -180,25 +195,38 @@ def test_chunked_prompt_full_size_prompt_workload_sampled():
     chunk_case(4, 32, 128, [1024] * 4, 410, 409, torch.bfloat16, 1.0, 59, attn=True, sample=8)
 
 
-def test_chunk_refused_after_an_eviction_and_allowed_after_reset():
+@pytest.mark.parametrize("attn", [False, True])
+def test_further_prompt_after_generated_tokens(attn):
+    """Prompt, generation steps (which evict in place, so slot order no longer follows
+    position order), a further prompt, more steps, again."""
+    chunk_case(2, 2, 128, [300, 200, ("steps", 40), 150, ("steps", 25), 64, 200, ("steps", 10)], 48, 48,
+               torch.float16, 1.0, 81, attn=attn)
+    chunk_case(1, 3, 64, [("steps", 70), 100, ("steps", 30), 100], 30, 20, torch.bfloat16, 1.0, 82, attn=attn)
+
+
+def test_chunk_after_restore_and_workspace_check():
     from paper_2306_14048_amd import binding as hb, synth
     dev = torch.device("cuda:0")
     B, Hh, d, dtype = 1, 2, 64, torch.float16
     Q, K, V = synth.make_prompt(B, Hh, 64, d, dtype, 1.0, dev, 3)
-    cache = hb.H2OCache(B, Hh, d, 8, 8, dtype, device=dev)
-    need = hb.h2o_prefill_chunk_workspace_bytes(cache.cfg, 64)
+    a = hb.H2OCache(B, Hh, d, 8, 8, dtype, device=dev)
+    b = hb.H2OCache(B, Hh, d, 8, 8, dtype, device=dev)
+    need = hb.h2o_prefill_chunk_workspace_bytes(a.cfg, 64)
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
-    hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, need)
-    qs, ks, vs = synth.make_steps(B, Hh, d, 1, dtype, 1.0, dev, 3)
+    hb.h2o_prefill_chunk(a.handle, Q, K, V, 64, ws, need)
+    qs, ks, vs = synth.make_steps(B, Hh, d, 5, dtype, 1.0, dev, 3)
     out = torch.empty((B, Hh, d), dtype=dtype, device=dev)
-    cache.decode_step(qs[0], ks[0], vs[0], out)            # evicts: slots are no longer in position order
+    for s in range(5):
+        a.decode_step(qs[s], ks[s], vs[s], out)            # evicts: slots are no longer in position order
+    Ka, Va, acc, pos = (x.clone() for x in a.views())
+    b.restore(Ka, Va, acc, pos, a.tokens_seen)             # a restored cache: slot order unknown
+    hb.h2o_prefill_chunk(a.handle, Q, K, V, 64, ws, need)
+    hb.h2o_prefill_chunk(b.handle, Q, K, V, 64, ws, need)
+    torch.cuda.synchronize()
+    for x, y in zip(a.views(), b.views()):
+        assert torch.equal(x, y)
+    assert a.tokens_seen == b.tokens_seen == 64 + 5 + 64
     with pytest.raises(hb.H2OError) as ei:
-        hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, need)
-    assert ei.value.status == hb.H2O_ESTATE
-    cache.reset()
-    hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, need)
-    assert cache.tokens_seen == 64
-    with pytest.raises(hb.H2OError) as ei:
-        hb.h2o_prefill_chunk(cache.handle, Q, K, V, 64, ws, 16)
+        hb.h2o_prefill_chunk(a.handle, Q, K, V, 64, ws, 16)
     assert ei.value.status == hb.H2O_ENOMEM
-    cache.close()
+    a.close(); b.close()
