@@ -32,6 +32,11 @@ MFMA_PEAK_TFLOPS = 2500.0       # dense bf16 / fp16 matrix peak of the part
 # Counters cannot be collected inside a timed run, so the figure is carried here.
 PROFILED_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 111.1e6, "opt30b_layer_f16": 391.7e6,
                           "stack32_f16": 888.4e6}
+# The step over a 4-bit cache is bound by the vector ALU: vector instructions per
+# launch (SQ_INSTS_VALU, same profiler runs) against what 256 CUs x 4 SIMDs x 16
+# lanes issue per second at 2.4 GHz (the 78.6 TFLOP/s fp64 figure at 2 flop per FMA).
+PROFILED_Q4_VALU_INSTS = {"opt6.7b_layer_f16": 3.187e6, "opt30b_layer_f16": 1.398e7}
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # same for one launch pair of the prompt-scoring passes (read + written)
 PROFILED_PREFILL_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 1191.2e6, "prefill_bf16": 778.7e6,
                                   "opt30b_layer_f16": 4227.1e6}
@@ -368,6 +373,12 @@ def main():
                            "bytes_per_launch": bytes_per_launch,
                            "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager}
         rec["decode_tokens_per_s"] = B / (dec_us * L * 1e-6)
+        if args.kv_bits == 4 and w.name in PROFILED_Q4_VALU_INSTS:
+            ops = PROFILED_Q4_VALU_INSTS[w.name] * 64 / (dec_us * 1e-6) / 1e12
+            rec["alu_roofline"] = {"bound": "alu", "achieved": ops, "peak": ALU_PEAK_TLANEOPS,
+                                   "unit": "T vector-instruction lanes/s", "frac": ops / ALU_PEAK_TLANEOPS,
+                                   "kernel": "decode_q4_kernel",
+                                   "vector_instructions_per_launch": PROFILED_Q4_VALU_INSTS[w.name]}
         if mfma_roofline is not None:
             rec["prefill_roofline"] = mfma_roofline
     else:
