@@ -189,6 +189,11 @@ def test_chunked_prompt_large_budget_and_chunks():
     chunk_case(1, 2, 128, [2048] * 3, 2048, 2048, torch.bfloat16, 1.0, 57)
 
 
+def test_chunked_prompt_largest_budget_long_chunks():
+    """Budget 4096 with 4096-token chunks (8192 candidates per compression), one head."""
+    chunk_case(1, 1, 128, [4096, 4096, 1000], 2048, 2048, torch.float16, 1.0, 60, attn=True)
+
+
 def test_chunked_prompt_full_size_prompt_workload_sampled():
     """The prompt-only workload's shape (batch 4, 32 heads, 4096 tokens, bf16, 20 % budget) in
     1024-token chunks with attention output, 8 sampled heads."""
