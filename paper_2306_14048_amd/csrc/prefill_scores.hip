@@ -286,6 +286,10 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
         // pass 1: keys r0.. are visible to the queries at positions >= r0; pass 2:
         // the queries up to position off+r0+BN-1 see the keys up to there
         const bool live = !MASKED || (COLSUM ? off + r0 + BN - 1 >= w0 : r0 <= off + w0 + 31);
+        // Of the tiles that touch the block's diagonal, a wave's own 32 rows straddle
+        // only one; those in front of it are fully visible to the wave and need no
+        // mask arithmetic (wave-uniform test).
+        const bool clear = COLSUM ? (off + r0 >= w0 + 31 && r0 + BN <= nq) : (r0 + BN - 1 <= off + w0);
         f32x16 acc[MB];
         if (live) {
             __builtin_amdgcn_s_setprio(2);
@@ -316,13 +320,15 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                 // m_run tracks the maximum of the raw products (c2 > 0 keeps the order);
                 // the scale is folded into the exponent's fma
                 if constexpr (MASKED) {
+                    if (!clear) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
+                        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                            if (j > off + srow) acc[mb][v] = -INFINITY;
-                        }
+                            for (int v = 0; v < 16; ++v) {
+                                const int j = r0 + mb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                                if (j > off + srow) acc[mb][v] = -INFINITY;
+                            }
+                    }
                 }
                 float mx = m_run;
 #pragma unroll
@@ -357,10 +363,12 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                         for (int e = 0; e < 4; ++e)
                             x[e] = fmaf(acc[mb][4 * gq + e], c2, -lv[e]);
                         if constexpr (MASKED) {
+                            if (!clear) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const int i = r0 + mb * 32 + 8 * gq + 4 * half + e;
-                                if (off + i < srow || i >= nq) x[e] = -INFINITY;
+                                for (int e = 0; e < 4; ++e) {
+                                    const int i = r0 + mb * 32 + 8 * gq + 4 * half + e;
+                                    if (off + i < srow || i >= nq) x[e] = -INFINITY;
+                                }
                             }
                         }
                         sum0 += __builtin_amdgcn_exp2f(x[0]) + __builtin_amdgcn_exp2f(x[2]);
