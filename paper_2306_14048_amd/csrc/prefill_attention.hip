@@ -340,13 +340,16 @@ __global__ __launch_bounds__(ANW * 64, 2) void prefill_attn_kernel(
 
         if (live) {
             if constexpr (MASKED) {
+                // a wave whose 32 queries all see the whole tile needs no mask (wave-uniform)
+                if (r0 + ABN - 1 > off + w0) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
+                    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int j = r0 + mb * 32 + 16 * (v >> 3) + 8 * half + (v & 7);
-                        if (j > off + srow) sacc[mb][v] = -INFINITY;
-                    }
+                        for (int v = 0; v < 16; ++v) {
+                            const int j = r0 + mb * 32 + 16 * (v >> 3) + 8 * half + (v & 7);
+                            if (j > off + srow) sacc[mb][v] = -INFINITY;
+                        }
+                }
             }
             float mx = m_run;
 #pragma unroll
