@@ -38,7 +38,7 @@ PROFILED_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 111.1e6, "opt30b_layer_f16": 391.
 PROFILED_Q4_VALU_INSTS = {"opt6.7b_layer_f16": 3.187e6, "opt30b_layer_f16": 1.398e7}
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # same for one launch pair of the prompt-scoring passes (read + written)
-PROFILED_PREFILL_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 1191.2e6, "prefill_bf16": 778.7e6,
+PROFILED_PREFILL_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 1187.3e6, "prefill_bf16": 776.0e6,
                                   "opt30b_layer_f16": 4227.1e6}
 
 
