@@ -169,6 +169,12 @@ def test_chunked_prompt_attention_output_refused_for_binary32():
     cache.close()
 
 
+@pytest.mark.parametrize("heavy,recent", [(1, 0), (0, 1), (1, 1), (2, 3)])
+def test_chunked_prompt_smallest_budgets(heavy, recent):
+    chunk_case(1, 3, 128, [5, 1, 3, ("steps", 6), 4, 1], heavy, recent, torch.float16, 1.0, 83)
+    chunk_case(1, 2, 64, [2, 7], heavy, recent, torch.bfloat16, 1.0, 84, attn=True)
+
+
 def test_chunked_prompt_heavy_only_and_window_only():
     chunk_case(1, 3, 128, [200, 200, 200], 80, 0, torch.float16, 1.0, 52)
     chunk_case(1, 3, 128, [200, 200, 200], 0, 80, torch.float16, 1.0, 53)

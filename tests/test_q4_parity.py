@@ -136,6 +136,12 @@ def test_q4_decode_budgets(n, T, heavy, recent):
     q4_case(1, 4, 128, n, T, heavy, recent, torch.float16, 1.0, 63)
 
 
+@pytest.mark.parametrize("heavy,recent", [(1, 0), (0, 1), (1, 1), (3, 2)])
+def test_q4_smallest_budgets(heavy, recent):
+    q4_case(1, 3, 128, 9, 14, heavy, recent, torch.float16, 1.0, 72)
+    q4_case(1, 3, 64, 0, 10, heavy, recent, torch.bfloat16, 1.0, 73)
+
+
 def test_q4_decode_large_budgets():
     q4_case(1, 2, 128, 1500, 16, 512, 512, torch.float16, 1.0, 64)       # 1024
     q4_case(1, 2, 128, 2300, 12, 1024, 1024, torch.bfloat16, 1.0, 65)    # the largest supported
