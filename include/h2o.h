@@ -190,7 +190,7 @@ size_t h2o_prefill_chunk_workspace_bytes(const h2o_config *cfg, int32_t m, int32
  * the accumulated scores (Algorithm 2's accumulate line; binary32 add of the
  * binary32 column sum); then cache + chunk are compressed to the budget by the
  * prompt rule of h2o_prefill_select (last `recent` positions, `heavy` best older
- * ones).  m = 1 is what h2o_decode_step computes (without the output); one
+ * ones).  m = 1 is the update h2o_decode_step makes to the cache; one
  * chunk holding the whole prompt on an empty cache is h2o_prefill_scores.
  *   Q, K, V   [batch, heads, m, head_dim] in cfg.dtype
  *   workspace >= h2o_prefill_chunk_workspace_bytes(cfg, m, out != NULL)
