@@ -615,6 +615,8 @@ hipError_t pick(const h2o_cache &c, const void *q, const void *kn, const void *v
     if (rounds <= 8) return launch_resident<DT, D, 8, 8>(c, q, kn, vn, out, st);
     if constexpr (UMAX > 8) {
         if (rounds <= 13) return launch_resident<DT, D, 8, 13>(c, q, kn, vn, out, st);
+        // two more rounds still fit the registers of two workgroups per CU
+        if (rounds <= 15) return launch_resident<DT, D, 8, 15>(c, q, kn, vn, out, st);
     }
     // Chunked: the ring depth that wastes the fewest rounds on the last chunk
     // (rounds past the occupied slots re-read the last row)
