@@ -688,3 +688,46 @@ def test_quantised_storage_arguments():
         o.prefill_chunk(x, x, x)                          # not defined with quantised storage
     with pytest.raises(RuntimeError):
         OracleHead(8, 2, 2, cap=16).token_codes(0)
+
+
+# ------------------------------------------------ invariants over random schedules
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@settings(max_examples=60, deadline=None)
+@given(seed=st.integers(0, 2 ** 31 - 1), heavy=st.integers(0, 6), recent=st.integers(0, 6),
+       schedule=st.lists(st.tuples(st.sampled_from(["chunk", "steps"]), st.integers(1, 9)), min_size=1, max_size=6),
+       f32=st.booleans(), policy=st.integers(0, 1), bits=st.sampled_from([0, 4]))
+def test_invariants_over_random_schedules(seed, heavy, recent, schedule, f32, policy, bits):
+    """Whatever mix of prompt chunks and generation steps: the cache never exceeds the
+    budget, holds everything while it is not full, always holds the recent window,
+    evicted tokens never return, scores are bounded by the queries that could have
+    scored the token, and attention mass is conserved."""
+    if heavy + recent == 0:
+        heavy = 1
+    if bits == 4:
+        schedule = [("steps", m) if kind == "chunk" else (kind, m) for kind, m in schedule]
+    d, k = 8, heavy + recent
+    N = sum(m for _, m in schedule)
+    Q, K, V = (as_stored(x, "f16") for x in make_inputs(seed % 100000, N, d, sigma=1.0))
+    o = OracleHead(d, heavy, recent, 0.4, score_f32=f32, cap=N, policy=policy, kv_bits=bits, group=4)
+    t, gone, prev = 0, set(), set()
+    for kind, m in schedule:
+        if kind == "chunk":
+            o.prefill_chunk(Q[t:t + m], K[t:t + m], V[t:t + m])
+            t += m
+        else:
+            for _ in range(m):
+                r = o.decode(Q[t], K[t], V[t])
+                assert np.all(np.isfinite(r.out))
+                t += 1
+        pos, sc = o.resident()
+        cur = set(pos.tolist())
+        assert o.t == t and len(cur) == min(t, k)
+        assert set(range(max(0, t - recent), t)) <= cur
+        assert not (cur & gone)
+        gone |= (prev | set(range(t))) - cur
+        assert np.all(sc >= 0) and np.all(sc <= (t - pos) * (1 + 1e-5))
+        assert abs(sc.sum() + o.evicted_mass - o.queries) <= (1e-4 if f32 else 1e-9) * max(t, 1)
+        assert o.queries == t
+        prev = cur
