@@ -215,6 +215,25 @@ def test_further_prompt_after_generated_tokens(attn):
     chunk_case(1, 3, 64, [("steps", 70), 100, ("steps", 30), 100], 30, 20, torch.bfloat16, 1.0, 82, attn=attn)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_schedules(seed):
+    """Seeded random mixes of prompt chunks and generation steps, random budgets."""
+    rng = np.random.default_rng(1000 + seed)
+    heavy, recent = int(rng.integers(0, 90)), int(rng.integers(0, 90))
+    if heavy + recent == 0:
+        recent = 7
+    schedule = []
+    for _ in range(int(rng.integers(3, 8))):
+        if rng.random() < 0.6:
+            schedule.append(int(rng.integers(1, 320)))
+        else:
+            schedule.append(("steps", int(rng.integers(1, 30))))
+    if not any(isinstance(x, int) for x in schedule):
+        schedule.append(64)
+    dt, d = [(torch.float16, 128), (torch.bfloat16, 128), (torch.float16, 64)][seed % 3]
+    chunk_case(1, 3, d, schedule, heavy, recent, dt, 1.0, 2000 + seed, rank=seed % 2, attn=bool(seed & 2))
+
+
 def test_chunk_after_restore_and_workspace_check():
     from paper_2306_14048_amd import binding as hb, synth
     dev = torch.device("cuda:0")
