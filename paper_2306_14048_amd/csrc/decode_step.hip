@@ -616,6 +616,7 @@ hipError_t pick(const h2o_cache &c, const void *q, const void *kn, const void *v
     if constexpr (UMAX > 8) {
         if (rounds <= 13) return launch_resident<DT, D, 8, 13>(c, q, kn, vn, out, st);
         // two more rounds still fit the registers of two workgroups per CU
+        if (rounds <= 14) return launch_resident<DT, D, 8, 14>(c, q, kn, vn, out, st);
         if (rounds <= 15) return launch_resident<DT, D, 8, 15>(c, q, kn, vn, out, st);
     }
     // Chunked: the ring depth that wastes the fewest rounds on the last chunk

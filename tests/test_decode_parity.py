@@ -106,6 +106,7 @@ def test_decode_dtypes_and_budgets(dt, d, n, T, heavy, recent):
     (2048, 2048, 4200, 3),   # the largest budget (needs the raised LDS limit)
     (1, 0, 9, 12), (0, 1, 9, 12), (1, 1, 3, 12), (4, 3, 7, 9),   # smallest budgets
     (209, 208, 500, 24),     # 417 slots: the first budget past thirteen rounds of eight waves
+    (224, 224, 600, 24),     # 448 slots: fourteen rounds
     (240, 240, 600, 24),     # 480 slots: fifteen rounds, the deepest register-resident ring
     (241, 240, 600, 24),     # 481 slots: chunked
 ])
