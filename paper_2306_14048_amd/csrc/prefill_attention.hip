@@ -115,8 +115,10 @@ template <int D>
 __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__restrict__ V,
                                                           uint16_t *__restrict__ Vt, int n, int npad)
 {
+    // rows go into LDS in 32-bit pieces; the pitch of D + 2 elements (an odd number of
+    // words) spreads the column reads below over the banks
     constexpr int PITCH = D + 2;
-    __shared__ uint16_t tile[ABN * PITCH];
+    __shared__ __align__(4) uint16_t tile[ABN * PITCH];
     const int head = blockIdx.x, j0 = blockIdx.y * ABN, tid = threadIdx.x;
     const uint16_t *Vh = V + (size_t)head * n * D;
     uint16_t *Vth = Vt + (size_t)head * D * npad;
@@ -125,9 +127,8 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__rest
         const int r = q / CPR, c = q % CPR;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (j0 + r < n) v = *reinterpret_cast<const uint4 *>(Vh + (size_t)(j0 + r) * D + c * 8);
-        const uint16_t *e = reinterpret_cast<const uint16_t *>(&v);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) tile[r * PITCH + c * 8 + i] = e[i];
+        unsigned *dst = reinterpret_cast<unsigned *>(tile + r * PITCH + c * 8);
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     }
     __syncthreads();
     for (int q = tid; q < D * (ABN / 8); q += 256) {
