@@ -166,6 +166,12 @@ def test_q4_full_size_layer_workload_sampled():
     q4_case(16, 32, 128, 2048, 64, 205, 205, torch.float16, 1.0, 71, prompt="scores", sample=12)
 
 
+def test_q4_long_run():
+    """Several cache turnovers: every slot is rewritten many times by quantised new tokens."""
+    q4_case(1, 4, 128, 100, 600, 20, 20, torch.float16, 1.0, 74)
+    q4_case(1, 2, 64, 0, 500, 33, 31, torch.bfloat16, 1.25, 75)
+
+
 def test_q4_heavy_tailed_keys():
     q4_case(1, 4, 128, 500, 48, 50, 50, torch.float16, 1.5, 69)
 
