@@ -285,6 +285,17 @@ int h2o_cache_restore(h2o_cache *cache, const void *K, const void *V,
                       const float *acc, const int32_t *pos,
                       int32_t tokens_seen, void *hip_stream);
 
+/*
+ * Positions "rolled" into the cache (Sec. 5.4 Q1 and the appendix comparing with
+ * StreamingLLM: inputs of unbounded length are handled with positions assigned
+ * inside the cache instead of positions in the text): rolled_out[batch, heads, k]
+ * (device, int32) receives for every occupied slot the rank of its token among
+ * the head's cached tokens in position order (0 = oldest), -1 for a free slot.
+ * What is done with them (positional encodings) lies outside this library.
+ * Errors: EINVAL, EHIP.
+ */
+int h2o_cache_rolled_positions(const h2o_cache *cache, int32_t *rolled_out, void *hip_stream);
+
 /* Number of tokens seen so far (prompt length + steps), or H2O_EINVAL. */
 int h2o_cache_tokens_seen(const h2o_cache *cache);
 

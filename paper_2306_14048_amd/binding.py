@@ -30,7 +30,7 @@ EXPORTS = (
     "h2o_decode_step", "h2o_cache_snapshot", "h2o_cache_restore", "h2o_cache_tokens_seen",
     "h2o_cache_regions", "h2o_status_str", "h2o_prefill_attention_workspace_bytes",
     "h2o_prefill_attention", "h2o_prefill_attention_scores", "h2o_prefill_chunk_workspace_bytes",
-    "h2o_prefill_chunk",
+    "h2o_prefill_chunk", "h2o_cache_rolled_positions",
 )
 
 
@@ -71,6 +71,7 @@ _lib.h2o_prefill_attention_scores.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz
 _lib.h2o_prefill_chunk_workspace_bytes.restype = _sz
 _lib.h2o_prefill_chunk_workspace_bytes.argtypes = [_cfgp, _i32, _i32]
 _lib.h2o_prefill_chunk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
+_lib.h2o_cache_rolled_positions.argtypes = [_vp, _vp, _vp]
 _lib.h2o_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.h2o_cache_snapshot.argtypes = [_vp, _vp, _vp, _vp]
 _lib.h2o_cache_restore.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
@@ -218,6 +219,11 @@ def h2o_cache_restore(cache, K, V, acc, pos, tokens_seen, stream=None) -> None:
                                   _stream(stream)), "h2o_cache_restore")
 
 
+def h2o_cache_rolled_positions(cache, rolled_out, stream=None) -> None:
+    _check(_lib.h2o_cache_rolled_positions(cache, _ptr(rolled_out), _stream(stream)),
+           "h2o_cache_rolled_positions")
+
+
 def h2o_cache_tokens_seen(cache) -> int:
     return int(_lib.h2o_cache_tokens_seen(cache))
 
@@ -302,6 +308,13 @@ class H2OCache:
         acc = torch.empty((B, Hh, self.budget), dtype=torch.float32, device=self.device)
         h2o_cache_snapshot(self.handle, pos, acc, stream)
         return pos, acc
+
+    def rolled_positions(self, stream=None):
+        """int32 [B, Hh, k]: rank of each occupied slot's token among the cached tokens by position."""
+        B, Hh = self.shape_heads
+        out = torch.empty((B, Hh, self.budget), dtype=torch.int32, device=self.device)
+        h2o_cache_rolled_positions(self.handle, out, stream)
+        return out
 
     def restore(self, K, V, acc, pos, tokens_seen, stream=None):
         h2o_cache_restore(self.handle, K, V, acc, pos, tokens_seen, stream)

@@ -305,6 +305,12 @@ int h2o_cache_restore(h2o_cache *cache, const void *K, const void *V, const floa
     return H2O_OK;
 }
 
+int h2o_cache_rolled_positions(const h2o_cache *cache, int32_t *rolled_out, void *hip_stream)
+{
+    if (!cache || !rolled_out) return H2O_EINVAL;
+    return hip_rc(h2o_launch_rolled_positions(*cache, rolled_out, static_cast<hipStream_t>(hip_stream)));
+}
+
 int h2o_cache_tokens_seen(const h2o_cache *cache) { return cache ? cache->t : H2O_EINVAL; }
 
 int h2o_cache_regions(const h2o_cache *cache, void **K, void **V, float **acc, int32_t **pos)

@@ -354,6 +354,33 @@ __global__ __launch_bounds__(256) void order_slots_kernel(const int32_t *__restr
     }
 }
 
+// rolled[head][slot] = how many cached tokens have a smaller position (-1 for a free slot)
+__global__ __launch_bounds__(256) void rolled_positions_kernel(const int32_t *__restrict__ pos_g, int k,
+                                                               int n_occ, int32_t *__restrict__ rolled)
+{
+    extern __shared__ int32_t pos_l[];
+    const size_t hoff = (size_t)blockIdx.x * k;
+    for (int s = threadIdx.x; s < n_occ; s += 256) pos_l[s] = pos_g[hoff + s];
+    __syncthreads();
+    for (int s = threadIdx.x; s < k; s += 256) {
+        int rank = -1;
+        if (s < n_occ) {
+            const int p = pos_l[s];
+            rank = 0;
+            for (int j = 0; j < n_occ; ++j) rank += pos_l[j] < p;
+        }
+        rolled[hoff + s] = rank;
+    }
+}
+
+hipError_t h2o_launch_rolled_positions(const h2o_cache &c, int32_t *rolled, hipStream_t st)
+{
+    const int n_occ = c.t < c.k ? c.t : c.k;
+    hipLaunchKernelGGL(rolled_positions_kernel, dim3(c.cfg.batch * c.cfg.heads), dim3(256),
+                       (size_t)(n_occ > 0 ? n_occ : 1) * sizeof(int32_t), st, c.pos, c.k, n_occ, rolled);
+    return hipGetLastError();
+}
+
 hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn, int m, int n_occ,
                              int32_t *order, void *Kcat, void *Vcat, float *base, int32_t *pos_cat,
                              hipStream_t st)

@@ -121,6 +121,7 @@ def test_error_codes_without_device(hb):
     assert lib.h2o_prefill_attention_scores(None, 0x1000, 0x1000, 0x1000, 8, 0x1000, 1 << 20, 0x1000,
                                             None, None) == hb.H2O_EINVAL
     assert lib.h2o_prefill_chunk(None, 0x1000, 0x1000, 0x1000, 8, 0x1000, 1 << 20, None, None) == hb.H2O_EINVAL
+    assert lib.h2o_cache_rolled_positions(None, 0x1000, None) == hb.H2O_EINVAL
     lib.h2o_cache_destroy(None)
     assert hb.h2o_status_str(0) == "ok"
     assert "unsupported" in hb.h2o_status_str(hb.H2O_EUNSUPPORTED)

@@ -252,3 +252,40 @@ def test_opt30b_layer_config_sampled_heads():
     from paper_2306_14048_amd import synth
     st = sampled_case(synth.WORKLOADS["opt30b_layer_f16"], 64, synth.BASE_SEED)
     assert st.head_steps == 64 * 1024
+
+
+@pytest.mark.parametrize("heavy,recent,n,T", [(20, 12, 0, 0), (20, 12, 0, 9), (20, 12, 100, 0), (20, 12, 100, 57),
+                                              (300, 333, 900, 40), (0, 7, 30, 30)])
+def test_rolled_positions(heavy, recent, n, T):
+    """The rank of every cached token among its head's cached tokens by position (what
+    position rolling assigns), against the order of the oracle's resident set."""
+    from paper_2306_14048_amd import binding as hb, synth
+    dev = torch.device("cuda:0")
+    B, Hh, d, dtype = 2, 2, 128, torch.float16
+    k = heavy + recent
+    heads = [(b, h) for b in range(B) for h in range(Hh)]
+    cache = hb.H2OCache(B, Hh, d, heavy, recent, dtype, device=dev)
+    scale = parity.oracle_scale(d)
+    if n:
+        Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, 1.0, dev, 31)
+        oracles, _ = parity.oracle_prefill_heads(Q.cpu(), K.cpu(), V.cpu(), heads, heavy, recent, scale, n + T)
+        Kc, Vc, acc, pos = parity.cache_state_from_oracles(oracles, B, Hh, k, K.cpu(), V.cpu())
+        cache.restore(Kc.to(dev), Vc.to(dev), acc.to(dev), pos.to(dev), n)
+    else:
+        oracles = {bh: OracleHead(d, heavy, recent, scale, score_f32=True, cap=max(T, 1)) for bh in heads}
+    if T:
+        qs, ks, vs = synth.make_steps(B, Hh, d, T, dtype, 1.0, dev, 31)
+        outs, snaps = parity.run_gpu_decode(cache, qs, ks, vs)
+        for (b, h) in heads:
+            parity.check_head_decode(oracles[(b, h)], qs[:, b, h].cpu(), ks[:, b, h].cpu(), vs[:, b, h].cpu(),
+                                     outs[:, b, h], snaps[:, b, h], recent, parity.OUT_TOL[dtype])
+    rolled = cache.rolled_positions().cpu().numpy()
+    pos = cache.snapshot()[0].cpu().numpy()
+    for (b, h) in heads:
+        order = oracles[(b, h)].resident()[0].tolist()            # ascending positions
+        rank = {p: i for i, p in enumerate(order)}
+        want = np.array([rank[int(p)] if p >= 0 else -1 for p in pos[b, h]], dtype=np.int32)
+        assert np.array_equal(rolled[b, h], want)
+        occupied = rolled[b, h][rolled[b, h] >= 0]
+        assert sorted(occupied.tolist()) == list(range(len(order)))
+    cache.close()
