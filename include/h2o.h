@@ -56,7 +56,8 @@ typedef enum h2o_status {
     H2O_EUNSUPPORTED = -2,  /* head_dim not in {64, 128}, budget or prompt too large */
     H2O_ENOMEM = -3,        /* caller-provided buffer too small */
     H2O_ESTATE = -4,        /* call not legal in the cache's current state */
-    H2O_EHIP = -5           /* the HIP runtime reported an error */
+    H2O_EHIP = -5,          /* the HIP runtime reported an error */
+    H2O_ESCRATCH = -6       /* request needs more than the library's built-in scratch */
 } h2o_status;
 
 typedef enum h2o_dtype { H2O_F32 = 0, H2O_F16 = 1, H2O_BF16 = 2 } h2o_dtype;
@@ -172,6 +173,28 @@ int h2o_prefill_select(h2o_cache *cache, const void *K, const void *V,
 int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K,
                        const void *V, int32_t n, void *workspace,
                        size_t ws_bytes, float *colsum_out, void *hip_stream);
+
+/*
+ * h2o_prefill_scores for callers that cannot allocate or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.
+ * Same arguments minus the workspace, same results; the row statistics and column
+ * sums live in a fixed array of H2O_NOALLOC_SCRATCH_BYTES bytes inside the
+ * library's device image (one copy per GPU, held until the process ends), so the
+ * call allocates nothing, on the device or through any library.
+ *   limit   h2o_prefill_workspace_bytes(cfg, n) <= H2O_NOALLOC_SCRATCH_BYTES, i.e.
+ *           batch * heads * n <= 2 097 152 (rounded to 256 bytes per array);
+ *           beyond it the call returns H2O_ESCRATCH and enqueues nothing
+ *   sharing every call on a GPU uses that GPU's one array: calls that overlap in
+ *           time on one GPU (different streams) race; calls on one stream do not.
+ *           The array keeps the previous call's contents; nothing in it needs to
+ *           start at zero.
+ * The device current at the call must be the one the cache lives on (as for every
+ * entry point that launches).  Errors: as h2o_prefill_scores, and ESCRATCH.
+ */
+#define H2O_NOALLOC_SCRATCH_BYTES (16u << 20)
+int h2o_prefill_scores_noalloc(h2o_cache *cache, const void *Q, const void *K,
+                               const void *V, int32_t n, float *colsum_out,
+                               void *hip_stream);
 
 /* Device bytes of scratch h2o_prefill_chunk needs for chunks of up to m tokens
  * (cache + chunk as one candidate list: K and V rows, old scores, positions,

@@ -16,6 +16,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libh2o_hip.so")
 
 H2O_OK, H2O_EINVAL, H2O_EUNSUPPORTED, H2O_ENOMEM, H2O_ESTATE, H2O_EHIP = 0, -1, -2, -3, -4, -5
+H2O_ESCRATCH = -6
+H2O_NOALLOC_SCRATCH_BYTES = 16 << 20
 H2O_F32, H2O_F16, H2O_BF16 = 0, 1, 2
 H2O_RANK_ACCUMULATED, H2O_RANK_AVERAGED = 0, 1
 H2O_MAX_BUDGET = 4096
@@ -30,7 +32,7 @@ EXPORTS = (
     "h2o_decode_step", "h2o_cache_snapshot", "h2o_cache_restore", "h2o_cache_tokens_seen",
     "h2o_cache_regions", "h2o_status_str", "h2o_prefill_attention_workspace_bytes",
     "h2o_prefill_attention", "h2o_prefill_attention_scores", "h2o_prefill_chunk_workspace_bytes",
-    "h2o_prefill_chunk", "h2o_cache_rolled_positions",
+    "h2o_prefill_chunk", "h2o_cache_rolled_positions", "h2o_prefill_scores_noalloc",
 )
 
 
@@ -64,6 +66,7 @@ _lib.h2o_cache_destroy.restype = None
 _lib.h2o_prefill_colsum.argtypes = [_cfgp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
 _lib.h2o_prefill_select.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp]
 _lib.h2o_prefill_scores.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
+_lib.h2o_prefill_scores_noalloc.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
 _lib.h2o_prefill_attention_workspace_bytes.restype = _sz
 _lib.h2o_prefill_attention_workspace_bytes.argtypes = [_cfgp, _i32]
 _lib.h2o_prefill_attention.argtypes = [_cfgp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp, _vp]
@@ -175,6 +178,12 @@ def h2o_prefill_scores(cache, Q, K, V, n, workspace, ws_bytes, colsum_out=None, 
     _check(_lib.h2o_prefill_scores(cache, _ptr(Q), _ptr(K), _ptr(V), int(n), _ptr(workspace),
                                    int(ws_bytes), _ptr(colsum_out), _stream(stream)),
            "h2o_prefill_scores")
+
+
+def h2o_prefill_scores_noalloc(cache, Q, K, V, n, colsum_out=None, stream=None) -> None:
+    _check(_lib.h2o_prefill_scores_noalloc(cache, _ptr(Q), _ptr(K), _ptr(V), int(n),
+                                           _ptr(colsum_out), _stream(stream)),
+           "h2o_prefill_scores_noalloc")
 
 
 def h2o_prefill_attention_workspace_bytes(cfg: h2o_config, n: int) -> int:

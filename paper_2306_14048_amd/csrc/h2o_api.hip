@@ -1,10 +1,39 @@
 // C ABI of the H2O hot path (declarations and contracts: include/h2o.h).
 // Host-side only: argument validation, carving the caller's device memory into
 // the four cache regions, state tracking (tokens seen), kernel launches.
+#include <mutex>
 #include <new>
 #include "h2o_internal.h"
 
+// Scratch of h2o_prefill_scores_noalloc: row statistics and column sums of one
+// prompt phase.  Every GPU the library runs on holds its own copy of this array
+// (at its own address) until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; the device address it yields is what
+// kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[H2O_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mu;
+void *scratch_ptr[MAX_DEVICES];      // device address of `scratch` per device, once resolved
+
+// Address of the current device's copy of `scratch` (resolved on first use on that
+// device; h2o_cache_init does it, so later calls only read the table).
+int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return H2O_EHIP;
+    if (dev < 0 || dev >= MAX_DEVICES) return H2O_EUNSUPPORTED;
+    std::lock_guard<std::mutex> guard(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return H2O_EHIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return H2O_OK;
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -69,6 +98,13 @@ int h2o_cache_init(const h2o_config *cfg, void *dev_mem, size_t bytes, void *hip
     if (bytes < l.total) return H2O_ENOMEM;
     h2o_cache *c = new (std::nothrow) h2o_cache;
     if (!c) return H2O_ENOMEM;
+    {
+        // resolve this device's built-in scratch now: the call that uses it may run
+        // where nothing may be looked up any more (stream capture)
+        void *unused = nullptr;
+        const int src = scratch_of_current_device(&unused);
+        if (src == H2O_EHIP) { delete c; return H2O_EHIP; }
+    }
     c->cfg = *cfg;
     c->scale = h2o_scale_of(*cfg);
     c->k = cfg->heavy + cfg->recent;
@@ -150,6 +186,24 @@ int h2o_prefill_scores(h2o_cache *cache, const void *Q, const void *K, const voi
     int rc = h2o_prefill_colsum(&cache->cfg, Q, K, n, workspace, ws_bytes, sums, hip_stream);
     if (rc != H2O_OK) return rc;
     return h2o_prefill_select(cache, K, V, sums, n, hip_stream);
+}
+
+int h2o_prefill_scores_noalloc(h2o_cache *cache, const void *Q, const void *K, const void *V,
+                               int32_t n, float *colsum_out, void *hip_stream)
+{
+    if (!cache || !V) return H2O_EINVAL;
+    if (cache->t != 0) return H2O_ESTATE;
+    if (n < 1) return H2O_EINVAL;
+    if (n > H2O_MAX_PROMPT) return H2O_EUNSUPPORTED;
+    const size_t need = h2o_prefill_workspace_bytes(&cache->cfg, n);
+    if (need == 0) return H2O_EUNSUPPORTED;
+    if (need > H2O_NOALLOC_SCRATCH_BYTES) return H2O_ESCRATCH;
+    void *ws = nullptr;
+    const int rc = scratch_of_current_device(&ws);
+    if (rc != H2O_OK) return rc;
+    // nothing in the scratch has to start at zero: both passes write every word
+    // they later read
+    return h2o_prefill_scores(cache, Q, K, V, n, ws, H2O_NOALLOC_SCRATCH_BYTES, colsum_out, hip_stream);
 }
 
 size_t h2o_prefill_attention_workspace_bytes(const h2o_config *cfg, int32_t n)
@@ -332,6 +386,7 @@ const char *h2o_status_str(int status)
     case H2O_ENOMEM: return "caller buffer too small";
     case H2O_ESTATE: return "call not legal in this cache state";
     case H2O_EHIP: return "HIP runtime error";
+    case H2O_ESCRATCH: return "request exceeds the library's built-in scratch";
     default: return "unknown status";
     }
 }
