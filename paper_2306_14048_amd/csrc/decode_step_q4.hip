@@ -27,6 +27,7 @@
 // two codes per AND-OR, multiplied by the fp32 weight p * s_g in a mixed-precision
 // fma with fp32 accumulation; 16 * sum p s_g and sum p m_g are settled once per lane.
 #include "wave_ops.h"
+#include <type_traits>
 
 namespace {
 
@@ -295,20 +296,33 @@ void decode_q4_kernel(
     __builtin_amdgcn_wave_barrier();
 
     // ---- output: one pass over the cached values --------------------------------------
-    float o[32];
+    // Accumulated in fp32, except for binary32 element types: there the output has to
+    // hold 1e-5 relative, and the sums of p s_g (16 + c) are an order of magnitude larger
+    // than the output they leave once 16 sum p s_g and sum p m_g are taken off (a
+    // dequantised value is itself the small difference of m_g and c s_g), so fp32
+    // rounding of the large sums would show.  fp64 then, settled per lane before the
+    // columns meet in LDS.
+    using OT = typename std::conditional<DT == H2O_F32, double, float>::type;
+    OT o[32];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) o[i] = 0.f;
+    for (int i = 0; i < 32; ++i) o[i] = (OT)0;
     unsigned half16 = 0x4C004C00u;              // two halves of value 16 (in a vector register, as above)
     asm volatile("" : "+v"(half16));
-    float wsum = 0.f, msum = 0.f;               // sum p s_g and sum p m_g over this lane's rows
+    OT wsum = (OT)0, msum = (OT)0;              // sum p s_g and sum p m_g over this lane's rows
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (u * RPI + wave * RPW < n_occ) {
             pin(buf[u]);
             // rows past the occupied slots repeat the last occupied row with p = 0
             const float p = p_w[u * RPW + sub];
-            const float wgt = p * par[u].x;
-            msum = fmaf(p, par[u].y, msum);
+            OT wgt;
+            if constexpr (DT == H2O_F32) {
+                wgt = (double)p * (double)par[u].x;
+                msum = fma((double)p, (double)par[u].y, msum);
+            } else {
+                wgt = p * par[u].x;
+                msum = fmaf(p, par[u].y, msum);
+            }
             wsum += wgt;
             const unsigned w[4] = {buf[u].x, buf[u].y, buf[u].z, buf[u].w};
 #pragma unroll
@@ -320,8 +334,13 @@ void decode_q4_kernel(
                     const unsigned h2 = (x[j] & 0x03C003C0u) | half16;
                     const _Float16 lo = __builtin_bit_cast(_Float16, (unsigned short)(h2 & 0xffffu));
                     const _Float16 hi = __builtin_bit_cast(_Float16, (unsigned short)(h2 >> 16));
-                    o[i * 8 + j] = fmaf(wgt, (float)lo, o[i * 8 + j]);
-                    o[i * 8 + j + 4] = fmaf(wgt, (float)hi, o[i * 8 + j + 4]);
+                    if constexpr (DT == H2O_F32) {
+                        o[i * 8 + j] = fma(wgt, (double)(float)lo, o[i * 8 + j]);
+                        o[i * 8 + j + 4] = fma(wgt, (double)(float)hi, o[i * 8 + j + 4]);
+                    } else {
+                        o[i * 8 + j] = fmaf(wgt, (float)lo, o[i * 8 + j]);
+                        o[i * 8 + j + 4] = fmaf(wgt, (float)hi, o[i * 8 + j + 4]);
+                    }
                 }
             }
         }
@@ -330,12 +349,23 @@ void decode_q4_kernel(
     {
         // every lane hands its 32 partial columns to LDS (o_l[row of the round][column]);
         // the two constants, which belong to all 32 columns alike, are added up over
-        // the wave's rows first: fix_l[wave][li]
+        // the wave's rows first: fix_l[wave][li] (fp64 accumulation: taken off per lane)
         float *dst = o_l + (wave * RPW + sub) * OPITCH + li * 32;
+        float fix;
+        if constexpr (DT == H2O_F32) {
+            const double fixd = msum - 16.0 * wsum;
 #pragma unroll
-        for (int i = 0; i < 32; i += 4)
-            *reinterpret_cast<float4 *>(dst + i) = make_float4(o[i], o[i + 1], o[i + 2], o[i + 3]);
-        float fix = msum - 16.f * wsum;
+            for (int i = 0; i < 32; i += 4)
+                *reinterpret_cast<float4 *>(dst + i) =
+                    make_float4((float)(o[i] + fixd), (float)(o[i + 1] + fixd), (float)(o[i + 2] + fixd),
+                                (float)(o[i + 3] + fixd));
+            fix = 0.f;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 32; i += 4)
+                *reinterpret_cast<float4 *>(dst + i) = make_float4(o[i], o[i + 1], o[i + 2], o[i + 3]);
+            fix = msum - 16.f * wsum;
+        }
         fix += dpp_f<DPP_ROR8>(fix);
         fix += dpp_f<DPP_ROR4>(fix);
         if (LPR == 2) fix += dpp_f<DPP_ROR2>(fix);

@@ -71,9 +71,9 @@ def run_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, scale=0.0, sampl
     for st in results:
         total.merge(st)
     print("\n[decode parity] B=%d Hh=%d d=%d n=%d T=%d H=%d R=%d %s: head-steps %d, near-tied %d, "
-          "excused %d, max out l2 %.2e linf %.2e, scores not bit-equal %d (max rel %.1e)"
+          "excused %d, max out l2 %.2e linf %.2e (%.2f of the allowance), scores not bit-equal %d (max rel %.1e)"
           % (B, Hh, d, n, T, heavy, recent, str(dtype).split(".")[-1], total.head_steps,
-             total.near_tied_steps, total.excused, total.max_out_l2, total.max_out_linf,
+             total.near_tied_steps, total.excused, total.max_out_l2, total.max_out_linf, total.max_out_frac,
              total.score_mismatch, total.max_score_rel), flush=True)
     assert total.excused <= max(1, int(0.001 * total.head_steps)) or total.excused == 0
     assert total.max_score_rel <= 1e-6
@@ -252,6 +252,97 @@ def test_opt30b_layer_config_sampled_heads():
     from paper_2306_14048_amd import synth
     st = sampled_case(synth.WORKLOADS["opt30b_layer_f16"], 64, synth.BASE_SEED)
     assert st.head_steps == 64 * 1024
+
+
+def device_prompt_then_steps(w, n_sample, seed, steps=None, kv_bits=0):
+    """The path the benchmark times, end to end on the device: h2o_prefill_scores on the
+    workload's prompt, then the workload's generation steps, nothing restored from the
+    oracle.  A sample of heads is followed by the oracle on the same tensors.
+
+    The device's stored scores start from its own column sums, which carry the
+    column-sum tolerance (COLSUM_RTOL relative), so two candidates whose oracle
+    values lie within SELECT_RTOL = 2 * COLSUM_RTOL of each other may be ordered
+    either way, at the prompt compression and at every later eviction that compares
+    prompt-seeded scores.  Steps excused inside the 1e-6 near-tie rule and steps
+    excused only by that wider band are reported apart; anything else fails."""
+    from paper_2306_14048_amd import binding as hb, synth
+    from tests.test_prefill_parity import COLSUM_ATOL, COLSUM_RTOL, SELECT_RTOL
+    dev = torch.device("cuda:0")
+    B, Hh, d, n, k = w.batch, w.heads, w.head_dim, w.prompt, w.budget
+    T = steps or w.steps
+    scale_d = parity.oracle_scale(d)
+    rng = np.random.default_rng(seed)
+    flat = sorted(rng.choice(B * Hh, n_sample, replace=False).tolist())
+    heads = [(i // Hh, i % Hh) for i in flat]
+    Q, K, V = synth.make_prompt(B, Hh, n, d, w.dtype, w.sigma, dev, seed)
+    cache = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev, kv_bits=kv_bits)
+    col = torch.empty((B, Hh, n), dtype=torch.float32, device=dev)
+    cache.prefill_scores(Q, K, V, colsum_out=col)
+    pos0 = cache.snapshot()[0]
+    bi = torch.tensor([b for b, _ in heads]); hi = torch.tensor([h for _, h in heads])
+    bd, hd = bi.to(dev), hi.to(dev)
+    Qs, Ks, Vs = Q[bd, hd].cpu(), K[bd, hd].cpu(), V[bd, hd].cpu()          # [S, n, d]
+    col_s, pos0_s = col[bd, hd].cpu().double().numpy(), pos0[bd, hd].cpu().numpy()
+    del Q, K, V, col
+    idx_heads = [(0, i) for i in range(n_sample)]
+    oracles, cols = parity.oracle_prefill_heads(Qs[None], Ks[None], Vs[None], idx_heads, w.heavy, w.recent,
+                                                scale_d, cap=n + T, kv_bits=kv_bits)
+    swapped_heads = swapped_tokens = 0
+    col_err = 0.0
+    for i in range(n_sample):
+        ref = cols[(0, i)]
+        err = np.abs(col_s[i] - ref) / (np.abs(ref) + COLSUM_ATOL / COLSUM_RTOL)
+        col_err = max(col_err, float(err.max()))
+        assert err.max() <= COLSUM_RTOL, "column sums of sampled head %d off by %.2e" % (i, err.max())
+        m = parity.adopt_kept_set(oracles[(0, i)], pos0_s[i], n - 1, w.recent, 0, SELECT_RTOL)
+        swapped_heads += int(m > 0)
+        swapped_tokens += m
+    qs, ks, vs = synth.make_steps(B, Hh, d, T, w.dtype, w.sigma, dev, seed)
+    outs, snaps = parity.run_gpu_decode(cache, qs, ks, vs, snapshot_heads=heads)
+    pos_f, acc_f = cache.snapshot()
+    torch.cuda.synchronize()
+    pos_f, acc_f = pos_f[bd, hd].cpu(), acc_f[bd, hd].cpu()
+    qh, kh, vh = qs[:, bd, hd].cpu(), ks[:, bd, hd].cpu(), vs[:, bd, hd].cpu()
+
+    def one(i):
+        st = parity.check_head_decode(oracles[(0, i)], qh[:, i], kh[:, i], vh[:, i], outs[:, i],
+                                      snaps[:, i], w.recent, parity.OUT_TOL[w.dtype], band=SELECT_RTOL)
+        parity.check_final_scores(oracles[(0, i)], pos_f[i], acc_f[i], st)
+        return st
+
+    results, _ = map_heads(one, range(n_sample))
+    total = parity.DecodeStats()
+    for st in results:
+        total.merge(st)
+    print("\n[device prompt phase + steps] %s, %d-bit cache: %d of %d heads x %d steps = %d head-steps; prompt: "
+          "max column-sum error %.2e, heads whose kept set differed at the threshold %d (%d tokens, oracle "
+          "re-synced, none dropped); steps: near-tied %d, excused inside 1e-6 %d, excused inside the "
+          "score band %.0e only %d, non-excused 0; max out l2 %.2e linf %.2e (%.2f of the allowance); final "
+          "scores max rel %.1e"
+          % (w.name, kv_bits or 16, n_sample, B * Hh, T, total.head_steps, col_err, swapped_heads,
+             swapped_tokens, total.near_tied_steps, total.excused, SELECT_RTOL, total.excused_band,
+             total.max_out_l2, total.max_out_linf, total.max_out_frac, total.max_score_rel), flush=True)
+    assert total.excused + total.excused_band <= max(1, int(0.001 * total.head_steps))
+    assert swapped_tokens <= max(1, int(0.001 * n_sample * k))
+    # stored scores = device column sum + correctly rounded probabilities
+    assert total.max_score_rel <= COLSUM_RTOL
+    cache.close()
+    return total
+
+
+def test_bench_path_device_prompt_then_steps_opt67b():
+    """Workload 2 exactly as the benchmark runs it (device prompt scoring + compression, then
+    256 fp16 steps, batch 16 x 32 heads), 64 sampled heads followed by the oracle."""
+    from paper_2306_14048_amd import synth
+    st = device_prompt_then_steps(synth.WORKLOADS["opt6.7b_layer_f16"], 64, synth.BASE_SEED + 1)
+    assert st.head_steps == 64 * 256
+
+
+def test_bench_path_device_prompt_then_steps_tiny():
+    """Workload 1 the same way: every head, every step."""
+    from paper_2306_14048_amd import synth
+    w = synth.WORKLOADS["tiny_f32"]
+    device_prompt_then_steps(w, w.batch * w.heads, synth.BASE_SEED + 2)
 
 
 @pytest.mark.parametrize("heavy,recent,n,T", [(20, 12, 0, 0), (20, 12, 0, 9), (20, 12, 100, 0), (20, 12, 100, 57),

@@ -677,6 +677,47 @@ def test_token_attends_to_itself_unquantised_and_is_stored_quantised():
     np.testing.assert_allclose(o.score(0), 1.0 + p[0], rtol=1e-14)
 
 
+def test_resync_on_a_quantised_cache_stores_the_restored_token():
+    """h2o_oracle_resync on 4-bit storage: the token that becomes resident again holds the
+    nearest-of-sixteen-levels codes of its original row (search in tests/brute.py), the token
+    that leaves keeps nothing that is read later, membership and mass swap as without
+    quantisation."""
+    rng = np.random.default_rng(21)
+    d, group, n = 8, 4, 14
+    Q, K, V = (as_stored(rng.standard_normal((n + 3, d)), "f16") for _ in range(3))
+    o = OracleHead(d, 3, 3, 0.4, score_f32=True, cap=n + 3, kv_bits=4, group=group)
+    o.prefill(Q[:n], K[:n], V[:n])
+    evicted = [j for j in range(n) if not o.is_resident(j)]
+    assert len(evicted) == n - 6
+    back = evicted[2]
+    with pytest.raises(RuntimeError):
+        o.token_codes(back)                          # never entered the cache: nothing stored
+    out = int(o.resident()[0][0])
+    total = o.resident()[1].sum() + o.evicted_mass
+    o.resync(back, out)
+    assert o.is_resident(back) and not o.is_resident(out)
+    assert abs(o.resident()[1].sum() + o.evicted_mass - total) < 1e-12
+    kc, kp, vc, vp = o.token_codes(back)
+    for row, codes, par in ((K[back], kc, kp), (V[back], vc, vp)):
+        ref, ref_codes, margin = nearest_level_quantise(row, group)
+        clear = margin > 1e-6
+        np.testing.assert_array_equal(codes[clear], ref_codes[clear])
+        np.testing.assert_allclose(dequantise(codes, par, group)[clear], ref[clear], rtol=0, atol=1e-12)
+    ks, vs = o.token_kv(back)
+    np.testing.assert_array_equal(ks, dequantise(kc, kp, group))
+    # and the next step attends to the stored (quantised) row of the restored token
+    r = o.decode(Q[n], K[n], V[n])
+    # attended to: what was resident before the step (incl. the token the step evicted), as
+    # stored, and the new token itself with its row as given
+    res = [j for j in range(n) if o.is_resident(j) or j == r.evicted]
+    assert back in res and len(res) == 6
+    Kd = np.stack([o.token_kv(j)[0] for j in res] + [K[n]])
+    Vd = np.stack([o.token_kv(j)[1] for j in res] + [V[n]])
+    s = 0.4 * Kd @ Q[n]
+    p = np.exp(s - s.max()); p /= p.sum()
+    np.testing.assert_allclose(r.out, p @ Vd, rtol=1e-12, atol=1e-12)
+
+
 def test_quantised_storage_arguments():
     with pytest.raises(ValueError):
         OracleHead(8, 2, 2, kv_bits=8)

@@ -48,7 +48,6 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
     Qc, Kc, Vc = Q.cpu(), K.cpu(), V.cpu()
     alive = set(heads)
     flips = 0
-    tol = parity.OUT_TOL[dtype] + parity.OUT_STORE_SLACK[dtype]
     c0 = 0                  # prompt tokens consumed
     s0 = 0                  # generation steps consumed
     t = 0                   # tokens seen
@@ -64,8 +63,8 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
                     o = oracles[(b, h)]
                     r = o.decode(parity.host64(qs[s, b, h]), parity.host64(ks[s, b, h]),
                                  parity.host64(vs[s, b, h]))
-                    err = np.linalg.norm(o_gpu[b, h] - r.out) / max(np.linalg.norm(r.out), 1e-300)
-                    assert err <= tol, "output of a step after chunked prompt off by %.2e" % err
+                    f_l2, f_el, err, _ = parity.output_error(o_gpu[b, h], r.out, dtype)
+                    assert f_l2 <= 1.0 and f_el <= 1.0, "output of a step after chunked prompt off by %.2e" % err
                     gp = set(pos[b, h][pos[b, h] >= 0].tolist())
                     if gp != set(o.resident()[0].tolist()):
                         # scores carry the column-sum tolerance: a near-tie may break the other way
@@ -127,7 +126,9 @@ def chunk_case(B, Hh, d, chunks, heavy, recent, dtype, sigma, seed, rank=0, deco
           % (B, Hh, d, shown if len(shown) < 8 else "%dx%s" % (len(shown), shown[0]), heavy, recent,
              str(dtype).split(".")[-1], rank, len(heads), len(heads) - len(alive),
              ", attention rows l2 %.2e linf %.2e" % tuple(out_max) if attn else ""), flush=True)
-    assert len(alive) >= 0.9 * len(heads)
+    # observed: no head ever dropped; one is allowed (the column sums behind the scores
+    # carry a tolerance), or 0.1 % of the head-chunks if that is more
+    assert len(heads) - len(alive) <= max(1, len(heads) * len(sizes) // 1000)
     cache.close()
     return flips
 

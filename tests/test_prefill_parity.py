@@ -11,11 +11,18 @@ pytestmark = pytest.mark.gpu
 
 torch_dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
-# Column sums: relative 1e-4 (fp32 accumulation of exact 16-bit products over
-# d <= 128 terms, logits of magnitude <= ~1e2, exp2/log2 hardware approximations:
-# ~1e-5 expected), plus an absolute floor for sums that underflow binary32.
-COLSUM_RTOL = 1e-4
+# Column sums: the device forms the logits on the matrix cores (exact products of
+# 16-bit inputs, fp32 accumulation over d <= 128 terms), scales and exponentiates in
+# fp32 (v_exp_f32 / v_log_f32, about 1 ulp each) at logits of magnitude up to ~1e2,
+# where one fp32 ulp of the scaled logit is already 8e-6 relative in the exponential,
+# and adds up to n terms in fp32.  Measured over every case of this file and the
+# full-size workloads: at most 1.0e-5 relative (binary32 inputs; 7.6e-6 for 16-bit
+# inputs).  The bar is three times that, plus an absolute floor for sums that
+# underflow binary32; every case prints its measured maximum.
+COLSUM_RTOL = 3e-5
 COLSUM_ATOL = 1e-30
+# Every softmax row sums to one, so a head's column sums add up to n (measured: 4e-7 n).
+ROW_MASS_RTOL = 2e-6
 # A token can change sides of the selection threshold only if its score is
 # within twice the column-sum tolerance of the threshold score.
 SELECT_RTOL = 2 * COLSUM_RTOL
@@ -52,7 +59,7 @@ def colsum_case(B, Hh, d, n, dtype, sigma, seed, scale=0.0):
     assert np.all(np.isfinite(got))
     assert err.max() <= 1.0, "column sums off by %.2f tolerances" % err.max()
     # every softmax row sums to one, so the column sums add up to n
-    assert np.abs(got.sum(-1) - n).max() <= 1e-4 * n
+    assert np.abs(got.sum(-1) - n).max() <= ROW_MASS_RTOL * n
     return got, ref
 
 
@@ -162,9 +169,12 @@ def scores_case(B, Hh, d, n, heavy, recent, dtype, sigma, seed):
     oracles, cols = parity.oracle_prefill_heads(Q.cpu(), K.cpu(), V.cpu(), heads, heavy, recent,
                                                 scale_d, cap=n)
     flips = 0
+    worst = 0.0
     for (b, h) in heads:
         ref = cols[(b, h)]
-        assert np.all(np.abs(col[b, h] - ref) <= COLSUM_RTOL * np.abs(ref) + COLSUM_ATOL)
+        worst = max(worst, float((np.abs(col[b, h] - ref) / (np.abs(ref) + COLSUM_ATOL / COLSUM_RTOL)).max()))
+        assert np.all(np.abs(col[b, h] - ref) <= COLSUM_RTOL * np.abs(ref) + COLSUM_ATOL), \
+            "column sums off by %.2e relative" % worst
         rp, rs = oracles[(b, h)].resident()
         gp = pos[b, h][pos[b, h] >= 0]
         assert len(gp) == len(rp) == min(n, k)
@@ -180,8 +190,8 @@ def scores_case(B, Hh, d, n, heavy, recent, dtype, sigma, seed):
                 assert abs(ref[j] - thr) <= SELECT_RTOL * thr, \
                     "token %d (score %.9g) changed sides of threshold %.9g" % (j, ref[j], thr)
             flips += len(diff) // 2
-    print("\n[prefill] B=%d Hh=%d d=%d n=%d H=%d R=%d %s: heads %d, threshold flips %d"
-          % (B, Hh, d, n, heavy, recent, str(dtype).split(".")[-1], len(heads), flips), flush=True)
+    print("\n[prefill] B=%d Hh=%d d=%d n=%d H=%d R=%d %s: heads %d, max column-sum error %.2e, threshold flips %d"
+          % (B, Hh, d, n, heavy, recent, str(dtype).split(".")[-1], len(heads), worst, flips), flush=True)
     cache.close()
     return flips
 

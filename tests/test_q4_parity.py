@@ -67,12 +67,14 @@ def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="s
         torch.cuda.synchronize()
         if prompt != "select":
             # the device's own column sums: a token at the selection threshold may change sides
+            # (only there: every token that changes sides lies within the selection band of the
+            # oracle's threshold, and the oracle then adopts the device's set, re-quantising the
+            # rows that enter; no head is dropped)
+            from tests.test_prefill_parity import SELECT_RTOL
             pos = cache.views()[3].cpu().numpy()
-            same = [bh for bh in heads
-                    if set(pos[bh][pos[bh] >= 0].tolist()) == set(oracles[bh].resident()[0].tolist())]
-            assert len(same) >= 0.9 * len(heads)
-            oracles = {bh: oracles[bh] for bh in same}
-            heads = same
+            swapped = sum(parity.adopt_kept_set(oracles[bh], pos[bh], n - 1, recent, rank, SELECT_RTOL)
+                          for bh in heads)
+            assert swapped <= max(1, len(heads) * k // 1000)
         rows = check_stored_rows(hb, cache, oracles, d)
         assert rows == len(heads) * min(n, k)
     else:
@@ -86,10 +88,15 @@ def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="s
     pos_f, acc_f = (x.cpu() for x in cache.snapshot())
     qs, ks, vs = qs.cpu(), ks.cpu(), vs.cpu()
 
+    # scores seeded by the device's own column sums carry that pass's tolerance, and so
+    # does the order of two candidates whose values are closer than twice that
+    from tests.test_prefill_parity import SELECT_RTOL
+    band = parity.NEAR_TIE if prompt == "select" or n == 0 else SELECT_RTOL
+
     def one(bh):
         b, h = bh
         st = parity.check_head_decode(oracles[bh], qs[:, b, h], ks[:, b, h], vs[:, b, h], outs[:, b, h],
-                                      snaps[:, b, h], recent, parity.OUT_TOL[dtype], policy=rank)
+                                      snaps[:, b, h], recent, parity.OUT_TOL[dtype], policy=rank, band=band)
         parity.check_final_scores(oracles[bh], pos_f[b, h], acc_f[b, h], st)
         return st
     res, _ = map_heads(one, heads)
@@ -102,9 +109,10 @@ def q4_case(B, Hh, d, n, T, heavy, recent, dtype, sigma, seed, rank=0, prompt="s
           % (B, Hh, d, n, T, heavy, recent, str(dtype).split(".")[-1], rank, total.head_steps,
              total.excused, total.max_out_l2, total.max_out_linf, total.score_mismatch,
              total.max_score_rel, rows), flush=True)
-    assert total.excused <= max(1, total.head_steps // 1000)
+    assert total.excused + total.excused_band <= max(1, total.head_steps // 1000)
     # scores seeded by the device's own column sums carry that pass's tolerance
-    assert total.max_score_rel <= (1e-6 if prompt == "select" else 1e-4)
+    from tests.test_prefill_parity import COLSUM_RTOL
+    assert total.max_score_rel <= (1e-6 if prompt == "select" else COLSUM_RTOL)
     cache.close()
     return total
 
