@@ -26,20 +26,35 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0       # dense bf16 / fp16 matrix peak of the part
-# HBM bytes per generation-step launch read back from the profiler's FETCH_SIZE /
-# WRITE_SIZE counters (each scaled by what the same counter reports for a plain
-# 256 MiB copy: x2.000 and x1.000), from the runs summarised under profiles/.
-# Counters cannot be collected inside a timed run, so the figure is carried here.
-PROFILED_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 111.1e6, "opt30b_layer_f16": 391.7e6,
-                          "stack32_f16": 888.4e6}
-# The step over a 4-bit cache is bound by the vector ALU: vector instructions per
-# launch (SQ_INSTS_VALU, same profiler runs) against what 256 CUs x 4 SIMDs x 16
-# lanes issue per second at 2.4 GHz (the 78.6 TFLOP/s fp64 figure at 2 flop per FMA).
-PROFILED_Q4_VALU_INSTS = {"opt6.7b_layer_f16": 3.187e6, "opt30b_layer_f16": 1.398e7}
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# same for one launch pair of the prompt-scoring passes (read + written)
-PROFILED_PREFILL_TRAFFIC_BYTES = {"opt6.7b_layer_f16": 1187.3e6, "prefill_bf16": 776.0e6,
-                                  "opt30b_layer_f16": 4227.1e6}
+# Cold-cache leg: this many independent caches of the workload are visited in turn,
+# so that every launch reads a cache that the 256 MB last-level cache cannot still hold.
+COLD_CACHES = 8
+LLC_BYTES = 256 << 20
+
+
+def profiled_figures():
+    """Figures that cannot be collected inside a timed run (hardware counters) come
+    from the rocprofv3 summaries under profiles/: every line of the form
+        bench-figure <name> <kernel> <workload> <value>
+    is one figure (HBM bytes per launch from FETCH_SIZE / WRITE_SIZE scaled by what
+    the same counters read for a plain 256 MiB copy; vector instructions per launch
+    from SQ_INSTS_VALU).  A figure no summary holds is reported as null."""
+    out = {}
+    pdir = os.path.join(ROOT, "profiles")
+    if os.path.isdir(pdir):
+        for fn in sorted(os.listdir(pdir)):
+            if not fn.endswith((".md", ".txt")):
+                continue
+            with open(os.path.join(pdir, fn)) as f:
+                for line in f:
+                    w = line.split()
+                    if len(w) == 5 and w[0] == "bench-figure":
+                        try:
+                            out[(w[1], w[2], w[3])] = float(w[4])
+                        except ValueError:
+                            pass
+    return out
 
 
 def decode_bytes_per_head_step(k: int, d: int, esize: int, kv_bits: int = 0) -> int:
@@ -138,6 +153,9 @@ def main():
     ap.add_argument("--workload", default="opt6.7b_layer_f16")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the cold-cache leg (the generation step rotating over %d independent "
+                         "caches so that no launch finds its cache in the last-level cache)" % COLD_CACHES)
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = all)")
     ap.add_argument("--prompt", choices=("scores", "attention", "chunked"), default="scores",
                     help="prompt phase: 'scores' = row statistics + column sums + compression (the "
@@ -163,6 +181,7 @@ def main():
 
     import torch
     from paper_2306_14048_amd import binding as hb, synth
+    figures = profiled_figures()
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     w = synth.WORKLOADS[args.workload]
@@ -304,6 +323,51 @@ def main():
             stream.synchronize()
             dec_graph_us = e0.elapsed_time(e1) * 1e3 / (reps * T * L)
 
+        # Cold-cache leg of the generation step.  One layer's cache (C2: 108 MB) fits the
+        # 256 MB last-level cache, so the loop above may be served from there; here
+        # COLD_CACHES independent caches of the same workload are visited in turn (one
+        # graph of T x COLD_CACHES launches), so that a cache is re-read only after
+        # COLD_CACHES - 1 others of its size have been swept: the HBM-proof figure.
+        cold = None
+        if L == 1 and T > 0 and not args.no_cold and graph is not None:
+            cache_bytes = caches[0].nbytes
+            extra = []
+            n_ring = min(32, max(COLD_CACHES, -(-860_000_000 // cache_bytes)))   # >= ~0.86 GB swept per round
+            for _ in range(n_ring - 1):
+                c = hb.H2OCache(B, Hh, d, w.heavy, w.recent, w.dtype, device=dev, kv_bits=args.kv_bits)
+                hb.h2o_prefill_scores(c.handle, Qp, Kp, Vp, n, wsp, wsn, None, stream.cuda_stream)
+                extra.append(c)
+            hb.h2o_cache_reset(ptrs[0][0], stream.cuda_stream)
+            hb.h2o_prefill_scores(ptrs[0][0], Qp, Kp, Vp, n, wsp, wsn, None, stream.cuda_stream)
+            stream.synchronize()
+            ring = [ptrs[0][0]] + [c.handle for c in extra]
+            (_, qp, kp, vp) = ptrs[0]
+
+            def decode_ring(sp):
+                for s in range(T):
+                    off = s * step_stride
+                    for h in ring:
+                        hb.h2o_decode_step(h, qp + off, kp + off, vp + off, op + off, sp)
+            decode_ring(stream.cuda_stream)          # warm-up pass (t advances; the budget is already full)
+            stream.synchronize()
+            g3 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g3, stream=stream):
+                decode_ring(stream.cuda_stream)
+            g3.replay()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            best = float("inf")
+            for _ in range(3):
+                e0.record(stream)
+                g3.replay()
+                e1.record(stream)
+                stream.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e3 / (T * len(ring)))
+            cold = {"us_per_launch": best, "caches": len(ring), "working_set_bytes": cache_bytes * len(ring)}
+            for c in extra:
+                c.close()
+            del extra
+
     ms_per_step = dt * 1e3 / args.steps
     # generated tokens per second; a prompt-only workload counts prompt tokens
     tokens_per_s = B * (T if T else n) / (dt / args.steps)
@@ -312,7 +376,7 @@ def main():
         fl = 2 * prefill_flops_per_pass(n, d, B * Hh)
         tf = fl / (pre_pass_ms * 1e-3) / 1e12
         mfma_roofline = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": tf / MFMA_PEAK_TFLOPS, "traffic": PROFILED_PREFILL_TRAFFIC_BYTES.get(w.name),
+                         "frac": tf / MFMA_PEAK_TFLOPS, "traffic": figures.get(("traffic_bytes_per_launch_pair", "prefill_pass_kernel", w.name)),
                          "kernel": "prefill_pass_kernel (row statistics + column sums, two launches)",
                          "flops_per_launch_pair": fl, "ms_per_launch_pair": pre_pass_ms}
     if T > 0:
@@ -366,19 +430,34 @@ def main():
             % chunks[0][0].shape[2]
     if T > 0:
         # the dominant kernel: the generation step, HBM-bound
+        kname = "decode_resident_kernel" if args.kv_bits == 0 else "decode_q4_kernel"
+        ws_bytes = sum(c.nbytes for c in caches)
         rec["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": achieved / HBM_PEAK_GBS,
-                           "traffic": PROFILED_TRAFFIC_BYTES.get(w.name) if args.kv_bits == 0 else None,
-                           "kernel": "decode_resident_kernel" if args.kv_bits == 0 else "decode_q4_kernel",
+                           "traffic": figures.get(("traffic_bytes_per_launch", kname, w.name)),
+                           "kernel": kname,
                            "bytes_per_launch": bytes_per_launch,
-                           "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager}
+                           "us_per_launch": dec_us, "us_per_launch_eager": dec_us_eager,
+                           "working_set_bytes": ws_bytes,
+                           "working_set": "fits the 256 MB last-level cache: see roofline_cold for the HBM-proof figure"
+                           if ws_bytes <= LLC_BYTES else "exceeds the 256 MB last-level cache"}
+        if cold is not None:
+            ach = bytes_per_launch / (cold["us_per_launch"] * 1e-6) / 1e9
+            rec["roofline_cold"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": ach / HBM_PEAK_GBS, "kernel": kname,
+                                    "bytes_per_launch": bytes_per_launch,
+                                    "us_per_launch": cold["us_per_launch"], "caches": cold["caches"],
+                                    "working_set_bytes": cold["working_set_bytes"],
+                                    "launch": "one hip-graph of %d steps x %d independent caches visited in turn"
+                                    % (T, cold["caches"])}
         rec["decode_tokens_per_s"] = B / (dec_us * L * 1e-6)
-        if args.kv_bits == 4 and w.name in PROFILED_Q4_VALU_INSTS:
-            ops = PROFILED_Q4_VALU_INSTS[w.name] * 64 / (dec_us * 1e-6) / 1e12
+        q4_valu = figures.get(("vector_instructions_per_launch", "decode_q4_kernel", w.name))
+        if args.kv_bits == 4 and q4_valu:
+            ops = q4_valu * 64 / (dec_us * 1e-6) / 1e12
             rec["alu_roofline"] = {"bound": "alu", "achieved": ops, "peak": ALU_PEAK_TLANEOPS,
                                    "unit": "T vector-instruction lanes/s", "frac": ops / ALU_PEAK_TLANEOPS,
                                    "kernel": "decode_q4_kernel",
-                                   "vector_instructions_per_launch": PROFILED_Q4_VALU_INSTS[w.name]}
+                                   "vector_instructions_per_launch": q4_valu}
         if mfma_roofline is not None:
             rec["prefill_roofline"] = mfma_roofline
     else:

@@ -125,6 +125,9 @@ size_t h2o_prefill_workspace_bytes(const h2o_config *cfg, int32_t n);
  * Creates a handle over caller-owned device memory `dev_mem` of `bytes` bytes
  * (>= h2o_cache_bytes) and enqueues the fill that marks every slot free
  * (pos = -1, acc = 0).  The cache starts empty with t = 0.
+ * This is the fixed-size, preallocated cache of App. A ("implementation details":
+ * the storage is allocated once at k = heavy + recent entries per head and never
+ * grows or moves; an evicted entry is overwritten in place, Sec. 4.2).
  * Errors: EINVAL, EUNSUPPORTED, ENOMEM (bytes too small), EHIP.
  */
 int h2o_cache_init(const h2o_config *cfg, void *dev_mem, size_t bytes,
@@ -152,13 +155,15 @@ int h2o_prefill_colsum(const h2o_config *cfg, const void *Q, const void *K,
                        float *colsum_out, void *hip_stream);
 
 /*
- * Prompt compression (App. A: "K heavy hitters and K recent tokens ...
- * otherwise return all"): given a score per prompt token, keep the last
+ * Prompt compression (App. A: keep K heavy hitters and K recent tokens, or all
+ * tokens if the prompt is not longer than that): given a score per prompt token, keep the last
  * `recent` tokens and the `heavy` highest-scoring older ones (all n tokens if
  * n <= heavy + recent; equal scores: the higher position is kept; with
  * H2O_RANK_AVERAGED the older tokens are ranked by score[j] / (n - j)), copy their
  * K/V rows into slots in ascending position order, set acc/pos, mark the rest
  * free, and set t = n.  The cache must be empty (fresh or reset).
+ * The compression itself orders any finite scores correctly (negative ones and
+ * signed zeros included); generation steps that follow need them non-negative.
  *   K, V    [batch, heads, n, head_dim];   score  float [batch, heads, n]
  * Errors: EINVAL, EUNSUPPORTED, ESTATE (cache not empty), EHIP.
  */
@@ -286,6 +291,12 @@ int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K,
  *      scored p_self, competes and may itself be dropped);
  *   6. the chosen slot gets K = k_new, V = v_new, acc = p_self, pos = t.
  * Then t becomes t + 1.  The cache is read exactly once.
+ * The position t and the number of occupied slots min(t, k) are tracked on the
+ * host handle and passed to the kernel as launch arguments (they are the same
+ * for all heads).  A captured HIP graph therefore replays exactly the steps it
+ * captured, at the positions they had at capture: replaying it makes sense from
+ * the same starting state only (e.g. reset + prompt + steps captured together);
+ * it cannot be replayed to generate further tokens.
  * Errors: EINVAL, EHIP.
  */
 int h2o_decode_step(h2o_cache *cache, const void *q, const void *k_new,
@@ -301,12 +312,44 @@ int h2o_cache_snapshot(const h2o_cache *cache, int32_t *pos_out, float *acc_out,
  * generation from a state computed elsewhere): K, V [batch, heads, k, head_dim]
  * (with kv_bits = 4: [batch, heads, k, H2O_Q4_ROW_BYTES] bytes in the stored
  * layout), acc, pos [batch, heads, k] are copied in and t is set to `tokens_seen`.
- * Every pos must be -1 or in [0, tokens_seen) and unique within a head (not
- * checked on the device).  Errors: EINVAL, EHIP.
+ * Requirements on the state, for every head (what the library's own calls leave
+ * behind, and what every later call relies on without checking):
+ *   - the occupied slots are exactly the prefix [0, min(tokens_seen, k)): slots
+ *     fill in index order and are only ever overwritten in place, so a hole
+ *     (pos = -1 below that bound) or an occupied slot above it cannot arise, and
+ *     a step would attend to whatever the hole's rows hold;
+ *   - every other slot has pos = -1;
+ *   - occupied positions lie in [0, tokens_seen) and are distinct;
+ *   - scores are finite and not negative (they are sums of probabilities; the
+ *     eviction order of later steps is only defined for such values).
+ * None of this is checked here (the data is on the device and the call does not
+ * synchronise); h2o_cache_validate checks all of it on the device.
+ * Errors: EINVAL, EHIP.
  */
 int h2o_cache_restore(h2o_cache *cache, const void *K, const void *V,
                       const float *acc, const int32_t *pos,
                       int32_t tokens_seen, void *hip_stream);
+
+/*
+ * Checks the bookkeeping of every head against the requirements listed at
+ * h2o_cache_restore (one small kernel, enqueued on the stream): flags_out
+ * [batch, heads] (device, int32) receives 0 for a consistent head, else the sum of
+ *     H2O_BAD_HOLE       1  a free slot below min(t, k)
+ *     H2O_BAD_BEYOND     2  an occupied slot from min(t, k) on
+ *     H2O_BAD_RANGE      4  a position outside [0, t)
+ *     H2O_BAD_DUPLICATE  8  one position in two slots
+ *     H2O_BAD_SCORE     16  a negative, infinite or NaN score
+ * The caller reads the flags after synchronising (the Python binding's
+ * H2OCache.restore(validate=True) does, and raises).  Intended after
+ * h2o_cache_restore of a state from outside; states the library produced
+ * itself pass.  Errors: EINVAL, EHIP.
+ */
+#define H2O_BAD_HOLE 1
+#define H2O_BAD_BEYOND 2
+#define H2O_BAD_RANGE 4
+#define H2O_BAD_DUPLICATE 8
+#define H2O_BAD_SCORE 16
+int h2o_cache_validate(const h2o_cache *cache, int32_t *flags_out, void *hip_stream);
 
 /*
  * Positions "rolled" into the cache (Sec. 5.4 Q1 and the appendix comparing with

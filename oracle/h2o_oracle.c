@@ -267,9 +267,10 @@ static int evict_before(double a, int pa, double b, int pb)
  * One-shot compression of a prompt of n tokens whose scores are in acc[0..n):
  * if the prompt fits in the budget keep everything; otherwise keep the last
  * `recent` tokens and, among the older ones, evict the smallest
- * (score, position) repeatedly until `heavy` of them remain (App. A:
- * "K heavy hitters and K recent tokens", written as repeated single evictions
- * so that it is the same rule the generation steps use).
+ * (score, position) repeatedly until `heavy` of them remain (App. A's prompt
+ * rule: the best-scoring tokens plus the most recent ones are what the prompt
+ * phase hands on; written as repeated single evictions so that it is the same
+ * rule the generation steps use).
  */
 static void compress_prompt(h2o_oracle *o, int n)
 {

@@ -20,6 +20,7 @@ H2O_ESCRATCH = -6
 H2O_NOALLOC_SCRATCH_BYTES = 16 << 20
 H2O_F32, H2O_F16, H2O_BF16 = 0, 1, 2
 H2O_RANK_ACCUMULATED, H2O_RANK_AVERAGED = 0, 1
+H2O_BAD_HOLE, H2O_BAD_BEYOND, H2O_BAD_RANGE, H2O_BAD_DUPLICATE, H2O_BAD_SCORE = 1, 2, 4, 8, 16
 H2O_MAX_BUDGET = 4096
 H2O_MAX_PROMPT = 65536
 
@@ -33,6 +34,7 @@ EXPORTS = (
     "h2o_cache_regions", "h2o_status_str", "h2o_prefill_attention_workspace_bytes",
     "h2o_prefill_attention", "h2o_prefill_attention_scores", "h2o_prefill_chunk_workspace_bytes",
     "h2o_prefill_chunk", "h2o_cache_rolled_positions", "h2o_prefill_scores_noalloc",
+    "h2o_cache_validate",
 )
 
 
@@ -75,6 +77,7 @@ _lib.h2o_prefill_chunk_workspace_bytes.restype = _sz
 _lib.h2o_prefill_chunk_workspace_bytes.argtypes = [_cfgp, _i32, _i32]
 _lib.h2o_prefill_chunk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
 _lib.h2o_cache_rolled_positions.argtypes = [_vp, _vp, _vp]
+_lib.h2o_cache_validate.argtypes = [_vp, _vp, _vp]
 _lib.h2o_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.h2o_cache_snapshot.argtypes = [_vp, _vp, _vp, _vp]
 _lib.h2o_cache_restore.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp]
@@ -233,6 +236,10 @@ def h2o_cache_rolled_positions(cache, rolled_out, stream=None) -> None:
            "h2o_cache_rolled_positions")
 
 
+def h2o_cache_validate(cache, flags_out, stream=None) -> None:
+    _check(_lib.h2o_cache_validate(cache, _ptr(flags_out), _stream(stream)), "h2o_cache_validate")
+
+
 def h2o_cache_tokens_seen(cache) -> int:
     return int(_lib.h2o_cache_tokens_seen(cache))
 
@@ -286,18 +293,55 @@ class H2OCache:
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         return self._ws
 
+    # -- argument checks: a tensor of the wrong size behind a raw pointer would be an
+    # out-of-bounds device access, so the class refuses it on the host
+    def _expect(self, x, shape, dtype, what):
+        if x is None:
+            return
+        if not isinstance(x, torch.Tensor):
+            raise TypeError("%s: expected a tensor" % what)
+        if x.device != self.mem.device:
+            raise ValueError("%s lives on %s, the cache on %s" % (what, x.device, self.mem.device))
+        if x.dtype != dtype:
+            raise ValueError("%s has dtype %s, expected %s" % (what, x.dtype, dtype))
+        if tuple(x.shape) != tuple(shape):
+            raise ValueError("%s has shape %s, expected %s" % (what, tuple(x.shape), tuple(shape)))
+        if not x.is_contiguous():
+            raise ValueError("%s must be contiguous" % what)
+
+    def _expect_prompt(self, Q, K, V, names="Q K V"):
+        B, Hh = self.shape_heads
+        n = (Q if Q is not None else K).shape[-2]
+        for x, nm in zip((Q, K, V), names.split()):
+            self._expect(x, (B, Hh, n, self.cfg.head_dim), self.dtype, nm)
+        return n
+
+    def _stored_row_shape(self):
+        B, Hh = self.shape_heads
+        if self.cfg.kv_bits == 4:
+            return (B, Hh, self.budget, q4_row_bytes(self.cfg.head_dim)), torch.uint8
+        return (B, Hh, self.budget, self.cfg.head_dim), self.dtype
+
     def reset(self, stream=None):
         h2o_cache_reset(self.handle, stream)
 
     def prefill_scores(self, Q, K, V, colsum_out=None, stream=None):
-        n = Q.shape[-2]
+        n = self._expect_prompt(Q, K, V)
+        self._expect(colsum_out, (*self.shape_heads, n), torch.float32, "colsum_out")
         ws = self.workspace(n)
         h2o_prefill_scores(self.handle, Q, K, V, n, ws, ws.numel(), colsum_out, stream)
+
+    def prefill_scores_noalloc(self, Q, K, V, colsum_out=None, stream=None):
+        """The same on the library's built-in scratch (no workspace is allocated)."""
+        n = self._expect_prompt(Q, K, V)
+        self._expect(colsum_out, (*self.shape_heads, n), torch.float32, "colsum_out")
+        h2o_prefill_scores_noalloc(self.handle, Q, K, V, n, colsum_out, stream)
 
     def prefill_chunk(self, Q, K, V, out=None, stream=None):
         """The next Q.shape[-2] prompt tokens as one chunk ([batch, heads, m, head_dim],
         contiguous); `out` (same shape) receives the chunk's attention output if given."""
-        m = Q.shape[-2]
+        m = self._expect_prompt(Q, K, V)
+        self._expect(out, Q.shape, self.dtype, "out")
         need = h2o_prefill_chunk_workspace_bytes(self.cfg, m, out is not None)
         if need == 0:
             raise H2OError(H2O_EUNSUPPORTED, "h2o_prefill_chunk_workspace_bytes")
@@ -306,9 +350,14 @@ class H2OCache:
         h2o_prefill_chunk(self.handle, Q, K, V, m, self._ws, self._ws.numel(), out, stream)
 
     def prefill_select(self, K, V, score, stream=None):
-        h2o_prefill_select(self.handle, K, V, score, K.shape[-2], stream)
+        n = self._expect_prompt(None, K, V)
+        self._expect(score, (*self.shape_heads, n), torch.float32, "score")
+        h2o_prefill_select(self.handle, K, V, score, n, stream)
 
     def decode_step(self, q, k_new, v_new, out, stream=None):
+        shape = (*self.shape_heads, self.cfg.head_dim)
+        for x, nm in ((q, "q"), (k_new, "k_new"), (v_new, "v_new"), (out, "out")):
+            self._expect(x, shape, self.dtype, nm)
         h2o_decode_step(self.handle, q, k_new, v_new, out, stream)
 
     def snapshot(self, stream=None):
@@ -325,8 +374,28 @@ class H2OCache:
         h2o_cache_rolled_positions(self.handle, out, stream)
         return out
 
-    def restore(self, K, V, acc, pos, tokens_seen, stream=None):
+    def validate(self, stream=None) -> torch.Tensor:
+        """int32 [B, Hh] (device): 0 for every head whose bookkeeping is consistent, else the
+        H2O_BAD_* bits of h2o_cache_validate.  Enqueued; read it after synchronising."""
+        flags = torch.empty(self.shape_heads, dtype=torch.int32, device=self.device)
+        h2o_cache_validate(self.handle, flags, stream)
+        return flags
+
+    def restore(self, K, V, acc, pos, tokens_seen, stream=None, validate=False):
+        """Loads a complete state.  validate=True also checks it on the device
+        (synchronises) and raises ValueError for a state the steps cannot run on."""
+        rshape, rdtype = self._stored_row_shape()
+        self._expect(K, rshape, rdtype, "K")
+        self._expect(V, rshape, rdtype, "V")
+        self._expect(acc, (*self.shape_heads, self.budget), torch.float32, "acc")
+        self._expect(pos, (*self.shape_heads, self.budget), torch.int32, "pos")
         h2o_cache_restore(self.handle, K, V, acc, pos, tokens_seen, stream)
+        if validate:
+            flags = self.validate(stream).cpu()           # the copy synchronises
+            if bool(flags.any()):
+                bad = flags.nonzero()[0].tolist()
+                raise ValueError("restored state is inconsistent: head %s has flags %d (see "
+                                 "h2o_cache_validate)" % (tuple(bad), int(flags[tuple(bad)])))
 
     @property
     def tokens_seen(self) -> int:

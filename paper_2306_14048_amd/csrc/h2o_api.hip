@@ -359,6 +359,12 @@ int h2o_cache_restore(h2o_cache *cache, const void *K, const void *V, const floa
     return H2O_OK;
 }
 
+int h2o_cache_validate(const h2o_cache *cache, int32_t *flags_out, void *hip_stream)
+{
+    if (!cache || !flags_out) return H2O_EINVAL;
+    return hip_rc(h2o_launch_validate(*cache, flags_out, static_cast<hipStream_t>(hip_stream)));
+}
+
 int h2o_cache_rolled_positions(const h2o_cache *cache, int32_t *rolled_out, void *hip_stream)
 {
     if (!cache || !rolled_out) return H2O_EINVAL;

@@ -67,6 +67,9 @@ hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn,
 // rolled[B*Hh][k]: rank of every occupied slot's token among the cached tokens by position
 hipError_t h2o_launch_rolled_positions(const h2o_cache &c, int32_t *rolled, hipStream_t st);
 
+// flags[B*Hh]: 0 for a head whose bookkeeping is consistent, else a bit mask (h2o.h)
+hipError_t h2o_launch_validate(const h2o_cache &c, int32_t *flags, hipStream_t st);
+
 // ---- element types ----------------------------------------------------------
 // Raw storage views: f32 -> float, f16 -> _Float16, bf16 -> uint16_t bit pattern.
 template <int DT> struct Elem;

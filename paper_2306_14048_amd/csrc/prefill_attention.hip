@@ -34,6 +34,7 @@
 // apart; one group's matrix phase (P.V of the previous tile, then Q.K of this
 // one: 32 MFMAs) overlaps the other group's vector phase (softmax of its tile).
 #include "h2o_internal.h"
+#include "lds_copy.h"
 #include <type_traits>
 
 namespace {
@@ -41,7 +42,6 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -70,32 +70,6 @@ template <int DT> __device__ inline unsigned pack2(float a, float b)
         return *reinterpret_cast<const unsigned *>(&h);
     }
 }
-
-// 16-byte-per-lane copy global -> LDS without staging registers: lane l writes
-// LDS bytes [lds_base + 16 l, +16) from byte voff + soff of the buffer `rsrc`.
-__device__ inline void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
-                 :
-                 : "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_base)
-                 : "memory");
-}
-__device__ inline i32x4 make_rsrc(const void *base, unsigned bytes)
-{
-    const size_t b = reinterpret_cast<size_t>(base);
-    i32x4 r;
-    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)b);
-    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
-    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
-    r.w = 0x00020000;     // raw buffer, 32-bit data format; reads past the end return zero
-    return r;
-}
-template <int N> __device__ inline void dma_wait_upto()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-// barrier that drains this wave's LDS reads but leaves global requests in flight
-__device__ inline void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // value of the lane that shares this lane's query (lane ^ 32), combined with op
 __device__ inline float other_half(float x)

@@ -24,6 +24,7 @@
 // Everything is computed in base 2: x = (scale*log2 e) * <q,k>, the stored row
 // statistic is log2 of the row's normaliser.
 #include "h2o_internal.h"
+#include "lds_copy.h"
 #include <type_traits>
 
 namespace {
@@ -53,52 +54,6 @@ __device__ inline f32x16 mma(const uint4 &a, const uint4 &b, f32x16 acc)
         return acc;
     }
 }
-
-// Asynchronous 16-byte-per-lane copy global -> LDS (no registers in between): the
-// wave's 64 lanes fill 1 KiB of LDS starting at the wave-uniform byte offset
-// `lds_base`, lane l at +16*l, each from byte `voff + soff` of the buffer that
-// `rsrc` describes (voff per lane, soff wave-uniform: the per-tile advance costs
-// no vector instruction).  Written as inline assembly so that the compiler does
-// not order later LDS reads of the OTHER tile buffer behind it; completion is
-// awaited explicitly (dma_wait).
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-__device__ inline void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
-                 :
-                 : "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_base)
-                 : "memory");
-}
-// Raw buffer descriptor (no stride, no swizzle, 32-bit data format) over `bytes`
-// bytes at `base`; reads past the end return zero.
-__device__ inline i32x4 make_rsrc(const void *base, unsigned bytes)
-{
-    const size_t b = reinterpret_cast<size_t>(base);
-    i32x4 r;
-    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)b);
-    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
-    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
-    r.w = 0x00020000;
-    return r;
-}
-// Same for one dword per lane (lane l writes LDS word l from `lds_base`); lanes
-// that are switched off copy nothing.
-__device__ inline void dma4(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dword %0, %1, %2 offen lds"
-                 :
-                 : "v"(voff), "s"(rsrc), "s"(soff), "s"(lds_base)
-                 : "memory");
-}
-
-// Waits until at most N of this wave's vector-memory requests are outstanding.
-template <int N> __device__ inline void dma_wait_upto()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-// Workgroup barrier that first drains this wave's LDS reads (so that a buffer is
-// really free once every wave has passed) but leaves global requests in flight.
-__device__ inline void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 constexpr int NWV = 8;         // waves per workgroup
 constexpr int NTB = 3;         // streamed-tile buffers (copies run two tiles ahead)

@@ -381,6 +381,49 @@ hipError_t h2o_launch_rolled_positions(const h2o_cache &c, int32_t *rolled, hipS
     return hipGetLastError();
 }
 
+// flags[head] = bit mask of what is wrong with the head's bookkeeping (0 = consistent):
+//   1  a slot below n_occ is free (the occupied slots are not the prefix [0, n_occ))
+//   2  a slot from n_occ on is occupied
+//   4  a position outside [0, t)
+//   8  two slots hold the same position
+//  16  a score that is negative (sign bit set), infinite or NaN
+__global__ __launch_bounds__(256) void validate_kernel(const int32_t *__restrict__ pos_g,
+                                                       const float *__restrict__ acc_g, int k, int n_occ,
+                                                       int t, int32_t *__restrict__ flags)
+{
+    extern __shared__ int32_t pos_l[];
+    __shared__ int bad;
+    const size_t hoff = (size_t)blockIdx.x * k;
+    if (threadIdx.x == 0) bad = 0;
+    for (int s = threadIdx.x; s < k; s += 256) pos_l[s] = pos_g[hoff + s];
+    __syncthreads();
+    int mine = 0;
+    for (int s = threadIdx.x; s < k; s += 256) {
+        const int p = pos_l[s];
+        if (s < n_occ) {
+            if (p < 0) mine |= 1;
+            else if (p >= t) mine |= 4;
+            const unsigned a = __float_as_uint(acc_g[hoff + s]);
+            if (a >= 0x7f800000u) mine |= 16;          // sign bit, infinity or NaN
+            if (p >= 0)
+                for (int j = 0; j < s; ++j) mine |= (pos_l[j] == p) ? 8 : 0;
+        } else if (p != -1) {
+            mine |= 2;
+        }
+    }
+    if (mine) atomicOr(&bad, mine);                    // LDS atomic
+    __syncthreads();
+    if (threadIdx.x == 0) flags[blockIdx.x] = bad;
+}
+
+hipError_t h2o_launch_validate(const h2o_cache &c, int32_t *flags, hipStream_t st)
+{
+    const int n_occ = c.t < c.k ? c.t : c.k;
+    hipLaunchKernelGGL(validate_kernel, dim3(c.cfg.batch * c.cfg.heads), dim3(256),
+                       (size_t)c.k * sizeof(int32_t), st, c.pos, c.acc, c.k, n_occ, c.t, flags);
+    return hipGetLastError();
+}
+
 hipError_t h2o_launch_concat(const h2o_cache &c, const void *Kn, const void *Vn, int m, int n_occ,
                              int32_t *order, void *Kcat, void *Vcat, float *base, int32_t *pos_cat,
                              hipStream_t st)
