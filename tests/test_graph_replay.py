@@ -69,3 +69,79 @@ def test_captured_pass_replays_identically(mode):
                 assert torch.equal(chunk_out, ref_chunk_out)
             assert torch.isfinite(scratch)
     cache.close()
+
+
+def test_captured_stack_of_layer_caches_against_the_oracle():
+    """What the benchmark does for the 32-layer workload, at a small size: several layer
+    caches resident at once, the generation phase (every token step visits every layer's
+    cache in turn) captured as ONE HIP graph and replayed; before each replay the caches
+    are restored to the same starting state.  Every replay's outputs and final states must
+    equal the eager run's bit for bit, and the eager run is checked head by head against
+    the oracle."""
+    import numpy as np
+    from paper_2306_14048_amd import binding as hb, synth
+    from tests import parity
+    dev = torch.device("cuda:0")
+    L, B, Hh, d, n, T, H, R = 6, 2, 4, 128, 300, 12, 40, 40
+    dtype = torch.float16
+    k = H + R
+    heads = [(b, h) for b in range(B) for h in range(Hh)]
+    scale = parity.oracle_scale(d)
+    caches, starts, oracles, steps_in = [], [], [], []
+    for layer in range(L):
+        Q, K, V = synth.make_prompt(B, Hh, n, d, dtype, 1.0, dev, 55, layer=layer)
+        orc, _ = parity.oracle_prefill_heads(Q.cpu(), K.cpu(), V.cpu(), heads, H, R, scale, cap=n + T)
+        state = tuple(x.to(dev) for x in parity.cache_state_from_oracles(orc, B, Hh, k, K.cpu(), V.cpu()))
+        c = hb.H2OCache(B, Hh, d, H, R, dtype, device=dev)
+        caches.append(c); starts.append(state); oracles.append(orc)
+        steps_in.append(synth.make_steps(B, Hh, d, T, dtype, 1.0, dev, 55, layer=layer))
+    outs = torch.empty((L, T, B, Hh, d), dtype=dtype, device=dev)
+    snaps = torch.empty((L, T, B, Hh, k), dtype=torch.int32, device=dev)
+
+    def restore_all(stream):
+        for c, (Kc, Vc, acc, pos) in zip(caches, starts):
+            c.restore(Kc, Vc, acc, pos, n, stream=stream)
+
+    def generate(stream):
+        sp = stream.cuda_stream
+        for s in range(T):
+            for layer, c in enumerate(caches):
+                q, kk, v = steps_in[layer]
+                hb.h2o_decode_step(c.handle, q[s], kk[s], v[s], outs[layer, s], sp)
+                hb.h2o_cache_snapshot(c.handle, snaps[layer, s], None, sp)
+
+    stream = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(stream):
+        restore_all(stream)
+        generate(stream)
+        stream.synchronize()
+        ref_out, ref_snaps = outs.clone(), snaps.clone()
+        ref_state = [[x.clone() for x in c.views()] for c in caches]
+        # the eager run against the oracle, every layer, head and step
+        total = parity.DecodeStats()
+        for layer in range(L):
+            q, kk, v = (x.cpu() for x in steps_in[layer])
+            o_l, s_l = ref_out[layer].cpu(), ref_snaps[layer].cpu()
+            for (b, h) in heads:
+                total.merge(parity.check_head_decode(oracles[layer][(b, h)], q[:, b, h], kk[:, b, h], v[:, b, h],
+                                                     o_l[:, b, h], s_l[:, b, h], R, parity.OUT_TOL[dtype]))
+        assert total.head_steps == L * B * Hh * T and total.excused == 0
+        # captured once (t is a launch argument: the graph holds these T steps from this start)
+        restore_all(stream)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            generate(stream)
+        for rep in range(3):
+            restore_all(stream)                            # eager work between replays
+            outs.zero_(); snaps.zero_()
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            assert torch.equal(outs, ref_out), "replay %d: outputs differ from the eager run" % rep
+            assert torch.equal(snaps, ref_snaps), "replay %d: kept positions differ from the eager run" % rep
+            for c, ref in zip(caches, ref_state):
+                for x, y in zip(c.views(), ref):
+                    assert torch.equal(x, y), "replay %d: a layer's cache differs from the eager run" % rep
+    for c in caches:
+        c.close()
