@@ -78,6 +78,23 @@
  *     eviction are untouched.  Chunked prompt processing is not defined with
  *     quantised storage here (returns -1).
  *
+ *   - `protect` 1 / 2 (h2o_oracle_set_protect): what the eviction may not touch
+ *     is given by a sparse-attention pattern instead of "the last `recent`
+ *     positions" (Sec. 5.2 "Enhancing Baseline Techniques", Table 2: strided and
+ *     fixed Sparse Transformer patterns combined with heavy hitters).  The
+ *     paper prints accuracies only and no rule; the reading taken: the
+ *     positions the pattern lets the current query attend to are PROTECTED,
+ *     everything else in the cache competes on its accumulated score as
+ *     before.  With the query at position t and a token at position p:
+ *         strided: t - p < recent   or   (t - p) mod stride == 0
+ *         fixed:   p div stride == t div stride   or   p mod stride >= stride - recent
+ *     (`recent` is the width of the local band / of a block's summary
+ *     columns).  If the pattern covers every cached token, protection is void
+ *     for that eviction: the smallest (score, position) among all cached
+ *     tokens other than the new one goes.  The cache size stays heavy + recent.
+ *     The prompt phase evicts one token at a time by the same rule, with the
+ *     last prompt token as the query, until the budget is met.
+ *
  * Pins (tests/test_oracle_pins.py): brute-force set-function evaluation on tiny
  * inputs, reduction to textbook causal softmax attention when the budget
  * covers the sequence, harmonic-number closed form for equal logits, sliding
@@ -96,6 +113,8 @@ typedef struct h2o_oracle {
     double scale;       /* logit scale */
     int score_f32;      /* store accumulated scores in binary32 */
     int policy;         /* 0: rank by accumulated score, 1: by averaged score */
+    int protect;        /* 0: last `recent` positions, 1: strided pattern, 2: fixed pattern */
+    int stride;         /* period of the strided / fixed pattern */
     int cap;            /* maximum number of tokens this object can see */
     int t;              /* tokens seen so far == position of the next token */
     int n_resident;
@@ -263,6 +282,61 @@ static int evict_before(double a, int pa, double b, int pb)
     return (a < b) || (a == b && pa < pb);
 }
 
+/* Select what the eviction may not touch (0 recent window, 1 strided, 2 fixed
+ * sparse pattern of the given period). */
+int h2o_oracle_set_protect(h2o_oracle *o, int mode, int stride)
+{
+    if (!o || mode < 0 || mode > 2 || (mode != 0 && stride < 1)) return -1;
+    o->protect = mode;
+    o->stride = mode ? stride : 0;
+    return 0;
+}
+
+/* Does the protection rule cover the token at position p when the latest query
+ * sits at position t (p <= t)? */
+static int is_protected(const h2o_oracle *o, int p, int t)
+{
+    switch (o->protect) {
+    case 1:  return (t - p) < o->recent || (t - p) % o->stride == 0;
+    case 2:  return p / o->stride == t / o->stride || p % o->stride >= o->stride - o->recent;
+    default: return p > t - o->recent;
+    }
+}
+
+/*
+ * Pattern-protected eviction of ONE token after the query at position last_q:
+ * the smallest (rank value, position) among the cached tokens the pattern does
+ * not cover; if it covers them all, among all cached tokens except `exempt`
+ * (the token that has just arrived; -1: nobody).  Reports the number of
+ * candidates and the two lowest rank values like the generation step does.
+ */
+static int evict_one_protected(h2o_oracle *o, int last_q, int exempt, int *n_cand,
+                               double *lowest, double *second)
+{
+    int u = -1, cnt = 0;
+    double lo = INFINITY, se = INFINITY;
+    for (int pass = 0; pass < 2 && u < 0; ++pass) {
+        cnt = 0;
+        for (int j = 0; j <= last_q; ++j) {
+            if (!o->resident[j]) continue;
+            if (pass == 0 ? is_protected(o, j, last_q) : j == exempt) continue;
+            ++cnt;
+            const double rj = rank_score(o, j, last_q);
+            if (u < 0 || evict_before(rj, j, lo, u)) { se = lo; lo = rj; u = j; }
+            else if (rj < se) se = rj;
+        }
+    }
+    if (u >= 0) {
+        o->resident[u] = 0;
+        o->evicted_mass += o->acc[u];
+        --o->n_resident;
+    }
+    if (n_cand) *n_cand = cnt;
+    if (lowest) *lowest = lo;
+    if (second) *second = se;
+    return u;
+}
+
 /*
  * One-shot compression of a prompt of n tokens whose scores are in acc[0..n):
  * if the prompt fits in the budget keep everything; otherwise keep the last
@@ -278,6 +352,11 @@ static void compress_prompt(h2o_oracle *o, int n)
     o->n_resident = n;
     o->t = n;
     if (n <= o->budget) return;
+    if (o->protect != 0) {
+        /* pattern-protected: one eviction at a time, the last prompt token is the query */
+        while (o->n_resident > o->budget) evict_one_protected(o, n - 1, -1, NULL, NULL, NULL);
+        return;
+    }
     const int first_recent = n - o->recent;   /* window = [n-R, n) */
     int older = first_recent;                 /* resident tokens outside it */
     while (older > o->heavy) {
@@ -405,7 +484,9 @@ int h2o_oracle_prefill_chunk(h2o_oracle *o, const double *Q, const double *K,
     o->n_resident += m;
     o->t = t1;
 
-    if (o->n_resident > o->budget) {
+    if (o->protect != 0) {
+        while (o->n_resident > o->budget) evict_one_protected(o, t1 - 1, -1, NULL, NULL, NULL);
+    } else if (o->n_resident > o->budget) {
         const int first_recent = t1 - o->recent;  /* window = [t1-R, t1) */
         int older = 0;
         for (int j = 0; j < first_recent; ++j) older += o->resident[j];
@@ -490,7 +571,10 @@ int h2o_oracle_decode(h2o_oracle *o, const double *q, const double *k_new,
 
     int evicted = -1, n_cand = 0;
     double lowest = INFINITY, second = INFINITY;
-    if (o->n_resident > o->budget) {
+    if (o->protect != 0) {
+        if (o->n_resident > o->budget)
+            evicted = evict_one_protected(o, t, t, &n_cand, &lowest, &second);
+    } else if (o->n_resident > o->budget) {
         /* candidates: resident positions outside the window {t-R+1..t} */
         const int last_cand = t - o->recent;
         for (int j = 0; j <= last_cand; ++j) {

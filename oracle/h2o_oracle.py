@@ -55,6 +55,7 @@ def _load():
     lib.h2o_oracle_decode.argtypes = [P, D, D, D, D, I, D, D]
     lib.h2o_oracle_resync.argtypes = [P, ctypes.c_int, ctypes.c_int]
     lib.h2o_oracle_set_policy.argtypes = [P, ctypes.c_int]
+    lib.h2o_oracle_set_protect.argtypes = [P, ctypes.c_int, ctypes.c_int]
     lib.h2o_oracle_tokens_seen.argtypes = [P]
     lib.h2o_oracle_num_resident.argtypes = [P]
     lib.h2o_oracle_evicted_mass.argtypes = [P]
@@ -102,7 +103,7 @@ class OracleHead:
 
     def __init__(self, d: int, heavy: int, recent: int, scale: float | None = None,
                  score_f32: bool = False, cap: int = 4096, policy: int = 0, kv_bits: int = 0,
-                 group: int = 64):
+                 group: int = 64, protect: int = 0, stride: int = 0):
         self._lib = _load()
         self.d, self.heavy, self.recent = int(d), int(heavy), int(recent)
         self.budget = self.heavy + self.recent
@@ -114,6 +115,9 @@ class OracleHead:
             raise ValueError("bad oracle configuration")
         if self._lib.h2o_oracle_set_policy(self._h, int(policy)) != 0:
             raise ValueError("unknown eviction policy %r" % (policy,))
+        self.protect, self.stride = int(protect), int(stride)
+        if self._lib.h2o_oracle_set_protect(self._h, self.protect, self.stride) != 0:
+            raise ValueError("bad protection pattern: mode %r, stride %r" % (protect, stride))
         self.kv_bits, self.group = int(kv_bits), int(group)
         if self._lib.h2o_oracle_set_kv_bits(self._h, self.kv_bits, self.group) != 0:
             raise ValueError("unsupported cache storage: %r bits in groups of %r" % (kv_bits, group))

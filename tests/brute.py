@@ -51,7 +51,28 @@ def nearest_level_quantise(row, group):
     return out, codes, margin
 
 
-def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0, store=None):
+def pattern_cover(pattern, recent, t):
+    """The set of positions <= t a sparse-attention pattern lets the query at position t
+    attend to, by enumeration (Sparse Transformer's two patterns, each the union of a local
+    part and a periodic part).  pattern = ("strided", s): the last `recent` positions, and
+    every s-th position counted back from t.  pattern = ("fixed", s): the block of s
+    positions that contains t, and the last `recent` positions of every block."""
+    kind, s = pattern
+    cover = set()
+    if kind == "strided":
+        cover.update(range(max(0, t - recent + 1), t + 1))
+        cover.update(range(t, -1, -s))
+    elif kind == "fixed":
+        b0 = (t // s) * s
+        cover.update(range(b0, t + 1))
+        for start in range(0, t + 1, s):
+            cover.update(j for j in range(start + s - recent, start + s) if 0 <= j <= t)
+    else:
+        raise ValueError(kind)
+    return cover
+
+
+def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0, store=None, pattern=None):
     """Q, K, V: [N, d] for all N = n + T tokens.  Returns a dict with
     per-decode-step outputs, resident sets after every call, evicted tokens,
     prompt column sums and final scores.  `store` (row -> row) is what the cache
@@ -82,6 +103,15 @@ def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0
         acc[:n] = _store(colsum, score_dtype)
         if n <= k:
             member[:n] = True
+        elif pattern is not None:
+            # what the pattern covers for the last prompt query stays, topped up with the best
+            # of the rest; if it covers more than the budget, the best of what it covers
+            cover = sorted(pattern_cover(pattern, recent, n - 1))
+            rest = [j for j in range(n) if j not in set(cover)]
+            r = _rank(acc, list(range(n)), n - 1, policy, score_dtype)
+            best_first = lambda js: sorted(js, key=lambda j: (r[j], j), reverse=True)
+            kept = cover + best_first(rest)[:k - len(cover)] if len(cover) <= k else best_first(cover)[:k]
+            member[kept] = True
         else:
             member[n - recent:n] = True
             older = list(range(n - recent))
@@ -111,7 +141,11 @@ def brute_h2o(Q, K, V, n, heavy, recent, scale, score_dtype=np.float64, policy=0
         u = -1
         if G.sum() > k:
             members = np.flatnonzero(G).tolist()
-            allowed = [v for v in members if v <= t - recent]
+            if pattern is None:
+                allowed = [v for v in members if v <= t - recent]
+            else:
+                cover = pattern_cover(pattern, recent, t)
+                allowed = [v for v in members if v not in cover] or [v for v in members if v != t]
             r = _rank(acc, members, t, policy, score_dtype)
             best_f = None
             for v in allowed:                     # ascending position

@@ -772,3 +772,148 @@ def test_invariants_over_random_schedules(seed, heavy, recent, schedule, f32, po
         assert abs(sc.sum() + o.evicted_mass - o.queries) <= (1e-4 if f32 else 1e-9) * max(t, 1)
         assert o.queries == t
         prev = cur
+
+
+# ------------------------------- sparse-attention patterns as the protected set (+ heavy hitters)
+from tests.brute import pattern_cover  # noqa: E402
+
+PATTERN_MODE = {"strided": 1, "fixed": 2}
+
+
+def run_oracle_pattern(Q, K, V, n, heavy, recent, scale, pattern, score_f32=False, policy=0):
+    N, d = Q.shape
+    o = OracleHead(d, heavy, recent, scale, score_f32=score_f32, cap=N, policy=policy,
+                   protect=PATTERN_MODE[pattern[0]], stride=pattern[1])
+    sets, outs, evicted = [], [], []
+    if n > 0:
+        o.prefill(Q[:n], K[:n], V[:n])
+        sets.append(set(o.resident()[0].tolist()))
+    for t in range(n, N):
+        r = o.decode(Q[t], K[t], V[t])
+        outs.append(r.out); evicted.append(r.evicted)
+        sets.append(set(o.resident()[0].tolist()))
+    return o, dict(sets=sets, outs=np.array(outs), evicted=evicted)
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("f32,policy", [(False, 0), (True, 0), (True, 1)])
+@pytest.mark.parametrize("pattern", [("strided", 2), ("strided", 3), ("strided", 5), ("fixed", 3),
+                                     ("fixed", 4), ("fixed", 7)])
+@pytest.mark.parametrize("n,T,heavy,recent", [(10, 12, 2, 2), (0, 18, 3, 1), (13, 9, 1, 3), (16, 8, 4, 2),
+                                              (9, 10, 3, 0)])
+def test_pattern_protection_matches_brute_force(seed, f32, policy, pattern, n, T, heavy, recent):
+    """The brute force builds the covered set of every query by enumeration, keeps the prompt by
+    sorting, and evicts by evaluating F_score of every allowed removal."""
+    if pattern[0] == "fixed" and recent > pattern[1]:
+        pytest.skip("a block has fewer positions than summary columns asked for")
+    d = 4
+    Q, K, V = make_inputs(7000 + seed, n + T, d)
+    o, got = run_oracle_pattern(Q, K, V, n, heavy, recent, 0.5, pattern, score_f32=f32, policy=policy)
+    ref = brute_h2o(Q, K, V, n, heavy, recent, 0.5, np.float32 if f32 else np.float64, policy=policy,
+                    pattern=pattern)
+    assert got["sets"] == ref["sets"]
+    assert got["evicted"] == ref["evicted"]
+    np.testing.assert_allclose(got["outs"], ref["outs"], rtol=1e-12, atol=1e-12)
+
+
+def test_strided_pattern_worked_by_hand():
+    """Budget 1 + 1, strided pattern of period 2, band of 1.  Two tokens are loaded with scores
+    (1, 5); every later query gives each cached token and itself the same probability (q = 0).
+      t = 2: scores (4/3, 16/3, 1/3); the pattern covers {2} and {2, 0}; only token 1 competes
+             and goes although it has the highest score             -> {0, 2}
+      t = 3: scores 0: 5/3, 2: 2/3; covers {3} and {3, 1}; tokens 0 and 2 compete, 2 is lower -> {0, 3}
+      t = 4: covers {4} and {4, 2, 0}; only token 3 competes                                   -> {0, 4}
+      t = 5: covers {5} and {5, 3, 1}; 0 (score 2 + 1/3) and 4 (2/3) compete                   -> {0, 5}
+    (Under the recent-window rule token 0, the lowest score outside the window at t = 2, would
+    have gone first.)"""
+    d = 2
+    o = OracleHead(d, 1, 1, 1.0, cap=8, protect=1, stride=2)
+    o.load_and_select(np.ones((2, d)), np.ones((2, d)), np.array([1.0, 5.0]))
+    z, one = np.zeros(d), np.ones(d)
+    kept, ev = [], []
+    for _ in range(4):
+        r = o.decode(z, one, one)
+        kept.append(o.resident()[0].tolist()); ev.append(r.evicted)
+    assert ev == [1, 2, 3, 4]
+    assert kept == [[0, 2], [0, 3], [0, 4], [0, 5]]
+    assert abs(o.score(0) - (1.0 + 4 / 3.0)) < 1e-12
+    w = OracleHead(d, 1, 1, 1.0, cap=8)                      # the window rule on the same input
+    w.load_and_select(np.ones((2, d)), np.ones((2, d)), np.array([1.0, 5.0]))
+    assert w.decode(z, one, one).evicted == 0
+
+
+def test_fixed_pattern_worked_by_hand():
+    """Budget 2 + 1, fixed pattern with blocks of 3 and one summary column per block (positions
+    2, 5, 8, ...), from an empty cache, equal probabilities (q = 0).
+      t = 0..2 fill the cache; scores after t = 2: (11/6, 5/6, 1/3)
+      t = 3: scores (25/12, 13/12, 7/12, 1/4); covered: block {3}, summary {2}; 0 and 1 compete,
+             1 is lower                                                               -> {0, 2, 3}
+      t = 4: covered: block {3, 4}, summary {2}; only token 0 competes and goes, the highest
+             score of all                                                             -> {2, 3, 4}
+      t = 5: covered: block {3, 4, 5}, summary {2, 5}: everything, so protection is void and the
+             lowest score among the others goes: 2: 13/12, 3: 3/4, 4: 1/2             -> {2, 3, 5}"""
+    d = 2
+    o = OracleHead(d, 2, 1, 1.0, cap=8, protect=2, stride=3)
+    z, one = np.zeros(d), np.ones(d)
+    ev = [o.decode(z, one, one).evicted for _ in range(6)]
+    assert ev == [-1, -1, -1, 1, 0, 4]
+    assert o.resident()[0].tolist() == [2, 3, 5]
+    np.testing.assert_allclose(o.resident()[1], [13 / 12.0, 3 / 4.0, 1 / 4.0], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("f32", [False, True])
+def test_strided_pattern_with_a_period_longer_than_the_text_is_the_recent_window(f32):
+    """(t - p) mod stride == 0 then only holds for p = t, which the band covers anyway: the
+    pattern is exactly "the last `recent` positions".  Bit for bit, prompt phase included."""
+    Q, K, V = make_inputs(31, 40, 4)
+    for (n, heavy, recent) in [(20, 3, 4), (0, 2, 2), (25, 5, 1)]:
+        _, a = run_oracle_pattern(Q, K, V, n, heavy, recent, 0.5, ("strided", 1000), score_f32=f32)
+        _, b = run_oracle(Q, K, V, n, heavy, recent, 0.5, score_f32=f32)
+        assert a["sets"] == b["sets"] and a["evicted"] == b["evicted"]
+        assert np.array_equal(a["outs"], b["outs"])
+
+
+def test_fixed_pattern_with_one_block_is_plain_lowest_score_eviction():
+    """One block holding the whole text covers every cached token, so protection is always void:
+    the lowest score among the tokens other than the new one goes.  That is the recent-window
+    rule with a window of one (the new token) and the same total budget, once generation starts
+    from an empty cache."""
+    Q, K, V = make_inputs(32, 30, 4)
+    _, a = run_oracle_pattern(Q, K, V, 0, 3, 2, 0.5, ("fixed", 1000))
+    _, b = run_oracle(Q, K, V, 0, 4, 1, 0.5)
+    assert a["sets"] == b["sets"] and a["evicted"] == b["evicted"]
+    assert np.array_equal(a["outs"], b["outs"])
+
+
+@pytest.mark.parametrize("pattern", [("strided", 4), ("fixed", 5)])
+def test_pattern_protection_invariants(pattern):
+    """Cache size, one in / at most one out, an evicted token never returns, mass conservation;
+    and the point of the rule: a covered token is never evicted while an uncovered one is cached."""
+    Q, K, V = make_inputs(33, 90, 4, sigma=1.0)
+    n, heavy, recent = 30, 6, 3
+    k = heavy + recent
+    o = OracleHead(4, heavy, recent, 0.5, cap=90, protect=PATTERN_MODE[pattern[0]], stride=pattern[1])
+    o.prefill(Q[:n], K[:n], V[:n])
+    prev = set(o.resident()[0].tolist())
+    assert len(prev) == k
+    gone = set(range(n)) - prev
+    for t in range(n, 90):
+        r = o.decode(Q[t], K[t], V[t])
+        cur = set(o.resident()[0].tolist())
+        assert len(cur) == k and t in cur
+        assert cur - prev == {t} and len(prev - cur) == 1 and not (cur & gone)
+        cover = pattern_cover(pattern, recent, t)
+        before = prev | {t}
+        if r.evicted in cover:
+            assert before <= cover, "a covered token went while an uncovered one was cached"
+        gone |= prev - cur
+        prev = cur
+        pos, sc = o.resident()
+        assert abs(sc.sum() + o.evicted_mass - o.queries) < 1e-9
+
+
+def test_pattern_arguments():
+    with pytest.raises(ValueError):
+        OracleHead(4, 2, 2, 0.5, cap=8, protect=3, stride=2)
+    with pytest.raises(ValueError):
+        OracleHead(4, 2, 2, 0.5, cap=8, protect=1, stride=0)
