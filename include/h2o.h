@@ -70,6 +70,29 @@ typedef enum h2o_dtype { H2O_F32 = 0, H2O_F16 = 1, H2O_BF16 = 2 } h2o_dtype;
  * Attempts"); only the ranking changes, the stored scores stay accumulated. */
 typedef enum h2o_rank { H2O_RANK_ACCUMULATED = 0, H2O_RANK_AVERAGED = 1 } h2o_rank;
 
+/*
+ * What the eviction may not touch.  H2O_PROTECT_RECENT is the method: the last
+ * `recent` positions (Sec. 5.1 budget split, App. A).  The other two put a
+ * sparse-attention pattern in the window's place, the combination the paper
+ * evaluates in Sec. 5.2 ("Enhancing Baseline Techniques", Table 2) without giving
+ * a rule; the reading taken: the positions the pattern lets the current query (at
+ * position t) attend to are protected, every other cached token competes on its
+ * score as before.  For a token at position p:
+ *     H2O_PROTECT_STRIDED  t - p < recent  or  (t - p) mod stride == 0
+ *     H2O_PROTECT_FIXED    p div stride == t div stride  or  p mod stride >= stride - recent
+ * (`recent` is then the width of the local band / the number of summary columns
+ * per block; the cache still holds heavy + recent tokens).  If the pattern covers
+ * every cached token, protection is void for that eviction: the smallest
+ * (rank value, position) among the cached tokens goes (the new token itself is
+ * always kept in these two modes).  The prompt compression evicts by the same
+ * rule, one token at a time with the last prompt token as the query: it keeps
+ * what the pattern covers plus the best of the rest up to the budget, or, if the
+ * pattern covers more than the budget, the best of what it covers.
+ */
+typedef enum h2o_protect {
+    H2O_PROTECT_RECENT = 0, H2O_PROTECT_STRIDED = 1, H2O_PROTECT_FIXED = 2
+} h2o_protect;
+
 /* Largest supported budget (heavy + recent) and prompt length. */
 #define H2O_MAX_BUDGET 4096
 #define H2O_MAX_PROMPT 65536
@@ -108,6 +131,8 @@ typedef struct h2o_config {
     float scale;        /* logit scale; 0 selects 1/sqrt(head_dim) */
     int32_t rank;       /* h2o_rank; 0 = the method's accumulated score */
     int32_t kv_bits;    /* cached K/V storage: 0 = elements of `dtype`, 4 = 4-bit codes */
+    int32_t protect;    /* h2o_protect; 0 = the method's recent window */
+    int32_t stride;     /* period of the strided / fixed pattern (>= 1); ignored for protect = 0 */
 } h2o_config;
 
 typedef struct h2o_cache h2o_cache;   /* opaque host-side handle */
@@ -286,7 +311,8 @@ int h2o_prefill_attention_scores(h2o_cache *cache, const void *Q, const void *K,
  *   4. acc[j] += p_j (binary32 add of the binary32-rounded probability);
  *   5. if a slot is free the new token takes the lowest-indexed free slot;
  *      otherwise the occupied slot with the smallest (rank value, pos) among
- *      those with pos <= t - recent is evicted, the rank value being acc or,
+ *      those with pos <= t - recent (for the pattern modes of h2o_protect: among
+ *      those the pattern does not cover) is evicted, the rank value being acc or,
  *      for H2O_RANK_AVERAGED, the binary32 quotient acc / (t - pos + 1) (with recent == 0 the new token,
  *      scored p_self, competes and may itself be dropped);
  *   6. the chosen slot gets K = k_new, V = v_new, acc = p_self, pos = t.

@@ -20,6 +20,7 @@ H2O_ESCRATCH = -6
 H2O_NOALLOC_SCRATCH_BYTES = 16 << 20
 H2O_F32, H2O_F16, H2O_BF16 = 0, 1, 2
 H2O_RANK_ACCUMULATED, H2O_RANK_AVERAGED = 0, 1
+H2O_PROTECT_RECENT, H2O_PROTECT_STRIDED, H2O_PROTECT_FIXED = 0, 1, 2
 H2O_BAD_HOLE, H2O_BAD_BEYOND, H2O_BAD_RANGE, H2O_BAD_DUPLICATE, H2O_BAD_SCORE = 1, 2, 4, 8, 16
 H2O_MAX_BUDGET = 4096
 H2O_MAX_PROMPT = 65536
@@ -41,7 +42,8 @@ EXPORTS = (
 class h2o_config(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("heavy", ctypes.c_int32), ("recent", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("scale", ctypes.c_float), ("rank", ctypes.c_int32), ("kv_bits", ctypes.c_int32)]
+                ("scale", ctypes.c_float), ("rank", ctypes.c_int32), ("kv_bits", ctypes.c_int32),
+                ("protect", ctypes.c_int32), ("stride", ctypes.c_int32)]
 
 
 class H2OError(RuntimeError):
@@ -131,11 +133,12 @@ def unpack_q4_rows(rows: torch.Tensor, head_dim: int):
     return codes, par
 
 
-def make_config(batch, heads, head_dim, heavy, recent, dtype, scale=0.0, rank=0, kv_bits=0) -> h2o_config:
+def make_config(batch, heads, head_dim, heavy, recent, dtype, scale=0.0, rank=0, kv_bits=0,
+                protect=0, stride=0) -> h2o_config:
     if isinstance(dtype, torch.dtype):
         dtype = DTYPES[dtype]
     return h2o_config(int(batch), int(heads), int(head_dim), int(heavy), int(recent), int(dtype),
-                      float(scale), int(rank), int(kv_bits))
+                      float(scale), int(rank), int(kv_bits), int(protect), int(stride))
 
 
 def h2o_status_str(status: int) -> str:
@@ -257,8 +260,9 @@ class H2OCache:
     one cache; methods forward to the entry points of the same name."""
 
     def __init__(self, batch, heads, head_dim, heavy, recent, dtype=torch.float16, scale=0.0,
-                 device="cuda", stream=None, rank=0, kv_bits=0):
-        self.cfg = make_config(batch, heads, head_dim, heavy, recent, dtype, scale, rank, kv_bits)
+                 device="cuda", stream=None, rank=0, kv_bits=0, protect=0, stride=0):
+        self.cfg = make_config(batch, heads, head_dim, heavy, recent, dtype, scale, rank, kv_bits,
+                               protect, stride)
         self.dtype = dtype if isinstance(dtype, torch.dtype) else TORCH_DTYPES[dtype]
         self.device = torch.device(device)
         self.budget = int(heavy) + int(recent)

@@ -69,12 +69,15 @@ __device__ inline void wave_output_to_lds(float (&o)[EPL], float *o_l, int wave,
 // exact to rounding unless some logit exceeds s_self by ~709; then the
 // normaliser overflows, which is detected, and the step is redone with the true
 // maximum (a rare, workgroup-uniform branch).
-template <int DT, int D, int NW, int U>
+// PAT: a sparse-attention pattern is the protected set (cfg.protect != 0); the plain
+// recent-window build carries none of that code.
+template <int DT, int D, int NW, int U, bool PAT>
 __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
-    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank)
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank, int protect,
+    int stride)
 {
     using E = Elem<DT>;
     using T = typename E::T;
@@ -231,10 +234,24 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
     // The 64-bit key (score bits, position) of a finite non-negative score is
     // also a positive double with the same order, and "no candidate" is a NaN,
     // which fmin drops: the key reduction is a plain fp64 minimum.
-    unsigned long long key = NO_CANDIDATE;
-    if (owner && pos_j <= t - recent)                        // window after this step = {t-R+1..t}
-        key = ((unsigned long long)__float_as_uint(rank_value(acc_j, pos_j, t, rank)) << 32) |
-              (unsigned)pos_j;
+    // With a sparse-attention pattern as the protected set (protect != 0) the
+    // candidates are the slots the pattern does not cover; should it cover them
+    // all, protection is void and every slot competes: the minimum over all slots
+    // is reduced alongside (in the LDS words of the overflow path, idle by now).
+    unsigned long long key = NO_CANDIDATE, own_key = NO_CANDIDATE;
+    if constexpr (PAT) {
+        if (owner) {
+            own_key = ((unsigned long long)__float_as_uint(rank_value(acc_j, pos_j, t, rank)) << 32) |
+                      (unsigned)pos_j;
+            if (!is_protected(pos_j, t, recent, protect, stride)) key = own_key;
+        }
+        const double ka = wave_min_f64(__longlong_as_double((long long)own_key));
+        if (lane == 0) red_max[wave] = ka;
+    } else {
+        if (owner && pos_j <= t - recent)                    // window after this step = {t-R+1..t}
+            key = ((unsigned long long)__float_as_uint(rank_value(acc_j, pos_j, t, rank)) << 32) |
+                  (unsigned)pos_j;
+    }
     {
         const double kw = wave_min_f64(__longlong_as_double((long long)key));
         if (lane == 0) red_key[wave] = kw;
@@ -259,10 +276,19 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
         double wd = red_key[0];
 #pragma unroll
         for (int w = 1; w < NW; ++w) wd = fmin(wd, red_key[w]);
+        if constexpr (PAT) {
+            if (wd != wd) {                                  // the pattern covers every slot
+                wd = red_max[0];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) wd = fmin(wd, red_max[w]);
+                key = own_key;
+            }
+        }
         const unsigned long long win = (unsigned long long)__double_as_longlong(wd);
         const unsigned long long self_key =
             ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
-        const bool evict = wd == wd && (recent != 0 || win < self_key);
+        // (a pattern always covers the new token; with the plain window of width 0 it competes)
+        const bool evict = wd == wd && (PAT || recent != 0 || win < self_key);
         evicted_mine = evict && owner && key == win;         // keys are unique (positions are)
         const unsigned long long b = __ballot(evicted_mine);
         if (b != 0) tslot = __builtin_amdgcn_readlane(my_slot, __ffsll((long long)b) - 1);
@@ -296,12 +322,13 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_resident_kernel(
 // (key phase) and once for the probabilities (value phase; the normaliser is
 // only known after the last key chunk).  Scores and positions are read one
 // chunk ahead of their use.  Softmax shift and overflow fallback as above.
-template <int DT, int D, int NW, int U>
+template <int DT, int D, int NW, int U, bool PAT>
 __global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
-    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank, int chunks)
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank, int protect,
+    int stride, int chunks)
 {
     using E = Elem<DT>;
     using T = typename E::T;
@@ -452,8 +479,10 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
 #pragma unroll
         for (int i = 0; i < EPL; ++i) o[i] = ps * E::to_f(x[i]);
     }
-    unsigned long long best = NO_CANDIDATE;  // smallest (score, position) among this lane's slots
+    unsigned long long best = NO_CANDIDATE;  // smallest (score, position) among this lane's candidate slots
     int best_slot = 0;
+    unsigned long long best_all = NO_CANDIDATE;   // ... among all its slots (pattern modes: see the resident kernel)
+    int best_all_slot = 0;
     auto value_chunk = [&](int c, auto refill_tag) {
         constexpr bool REFILL = decltype(refill_tag)::value;
         const int slot = c * CH + my_sc;
@@ -470,7 +499,13 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
         if (lane < OWN) p_w[lane] = p_j;
         if (owner) {
             acc_g[hoff + slot] = acc_j;
-            if (pos_j <= t - recent) {                           // window after this step = {t-R+1..t}
+            if constexpr (PAT) {
+                const unsigned long long key =
+                    ((unsigned long long)__float_as_uint(rank_value(acc_j, pos_j, t, rank)) << 32) |
+                    (unsigned)pos_j;
+                if (!is_protected(pos_j, t, recent, protect, stride) && key < best) { best = key; best_slot = slot; }
+                if (key < best_all) { best_all = key; best_all_slot = slot; }
+            } else if (pos_j <= t - recent) {                    // window after this step = {t-R+1..t}
                 const unsigned long long key =
                     ((unsigned long long)__float_as_uint(rank_value(acc_j, pos_j, t, rank)) << 32) |
                     (unsigned)pos_j;
@@ -499,6 +534,10 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
         const double kw = wave_min_f64(__longlong_as_double((long long)best));
         if (lane == 0) red_key[wave] = kw;
     }
+    if constexpr (PAT) {
+        const double ka = wave_min_f64(__longlong_as_double((long long)best_all));
+        if (lane == 0) red_max[wave] = ka;
+    }
     lds_barrier();
 
     // ---- write-back -----------------------------------------------------------------
@@ -515,10 +554,19 @@ __global__ __launch_bounds__(NW * 64, 4) void decode_chunked_kernel(
         double wd = red_key[0];
 #pragma unroll
         for (int w = 1; w < NW; ++w) wd = fmin(wd, red_key[w]);
+        if constexpr (PAT) {
+            if (wd != wd) {                                  // the pattern covers every slot
+                wd = red_max[0];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) wd = fmin(wd, red_max[w]);
+                best = best_all;
+                best_slot = best_all_slot;
+            }
+        }
         const unsigned long long win = (unsigned long long)__double_as_longlong(wd);
         const unsigned long long self_key =
             ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
-        const bool evict = wd == wd && (recent != 0 || win < self_key);
+        const bool evict = wd == wd && (PAT || recent != 0 || win < self_key);
         // keys are unique (positions are); the lane that holds the winner also wrote
         // that slot's score above, so its stores below are ordered behind that one
         const unsigned long long b = __ballot(evict && best == win);
@@ -552,7 +600,7 @@ inline hipError_t raise_lds_limit(const void *kern, size_t smem, bool &raised)
 #define H2O_DECODE_ARGS                                                                         \
     c.K, c.V, c.acc, c.pos, static_cast<const char *>(q), static_cast<const char *>(kn),        \
         static_cast<const char *>(vn), static_cast<char *>(out), c.k, (c.t < c.k ? c.t : c.k),  \
-        c.t, c.cfg.recent, c.scale, c.cfg.rank
+        c.t, c.cfg.recent, c.scale, c.cfg.rank, c.cfg.protect, c.cfg.stride
 
 template <int DT, int D, int NW, int U>
 hipError_t launch_resident(const h2o_cache &c, const void *q, const void *kn, const void *vn,
@@ -562,7 +610,15 @@ hipError_t launch_resident(const h2o_cache &c, const void *q, const void *kn, co
     constexpr int OWN = U * (64 / LPR);
     constexpr size_t smem = (size_t)NW * OWN * (LPR + 1) * 8 + (size_t)NW * 24 +
                             (size_t)NW * OWN * 4 + (size_t)NW * D * 4 + 16;
-    auto kern = decode_resident_kernel<DT, D, NW, U>;
+    if (c.cfg.protect != H2O_PROTECT_RECENT) {
+        auto kern = decode_resident_kernel<DT, D, NW, U, true>;
+        static bool raised = false;
+        hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st, H2O_DECODE_ARGS);
+        return hipGetLastError();
+    }
+    auto kern = decode_resident_kernel<DT, D, NW, U, false>;
     static bool raised = false;
     hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);
     if (e != hipSuccess) return e;
@@ -583,7 +639,16 @@ hipError_t launch_chunked(const h2o_cache &c, const void *q, const void *kn, con
     const int chunks = (occ + CH - 1) / CH;
     const size_t smem = (size_t)NW * OWN * (LPR + 1) * 8 + (size_t)NW * chunks * OWN * 8 +
                         (size_t)NW * 24 + (size_t)NW * OWN * 4 + (size_t)NW * D * 4 + 16;
-    auto kern = decode_chunked_kernel<DT, D, NW, U>;
+    if (c.cfg.protect != H2O_PROTECT_RECENT) {
+        auto kern = decode_chunked_kernel<DT, D, NW, U, true>;
+        static bool raised = false;
+        hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st, H2O_DECODE_ARGS,
+                           chunks);
+        return hipGetLastError();
+    }
+    auto kern = decode_chunked_kernel<DT, D, NW, U, false>;
     static bool raised = false;
     hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(kern), smem, raised);
     if (e != hipSuccess) return e;

@@ -77,7 +77,8 @@ void decode_q4_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
     int32_t *__restrict__ pos_g, const char *__restrict__ q_g,
     const char *__restrict__ kn_g, const char *__restrict__ vn_g,
-    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank)
+    char *__restrict__ out_g, int k, int n_occ, int t, int recent, double scale, int rank, int protect,
+    int stride)
 {
     using E = Elem<DT>;
     using T = typename E::T;
@@ -389,21 +390,32 @@ void decode_q4_kernel(
     // ---- score update (Algorithm 2, accumulate line: binary32 add of the binary32
     // probability) and the eviction candidate: smallest (rank value, position) outside
     // the window
-    unsigned long long key = NO_CANDIDATE;
-    int key_slot = -1;
+    // (with a sparse-attention pattern as the protected set the candidates are the slots
+    // it does not cover; the minimum over all slots is reduced alongside for the case
+    // that it covers them all, in the LDS words of the overflow path, idle by now)
+    unsigned long long key = NO_CANDIDATE, key_all = NO_CANDIDATE;
+    int key_slot = -1, key_all_slot = -1;
 #pragma unroll
     for (int s = 0; s < SPL; ++s) {
         acc_j[s] += p_j[s];
-        if (owner[s] && pos_j[s] <= t - recent) {
+        if (owner[s]) {
             const unsigned long long c =
                 ((unsigned long long)__float_as_uint(rank_value(acc_j[s], pos_j[s], t, rank)) << 32) |
                 (unsigned)pos_j[s];
-            if (c < key) { key = c; key_slot = my_slot[s]; }
+            if (protect == H2O_PROTECT_RECENT ? pos_j[s] <= t - recent
+                                              : !is_protected(pos_j[s], t, recent, protect, stride)) {
+                if (c < key) { key = c; key_slot = my_slot[s]; }
+            }
+            if (protect != H2O_PROTECT_RECENT && c < key_all) { key_all = c; key_all_slot = my_slot[s]; }
         }
     }
     {
         const double kw = wave_min_f64(__longlong_as_double((long long)key));
         if (lane == 0) red_key[wave] = kw;
+    }
+    if (protect != H2O_PROTECT_RECENT) {
+        const double ka = wave_min_f64(__longlong_as_double((long long)key_all));
+        if (lane == 0) red_max[wave] = ka;
     }
     lds_barrier();
 
@@ -427,10 +439,17 @@ void decode_q4_kernel(
         double wd = red_key[0];
 #pragma unroll
         for (int w = 1; w < NW; ++w) wd = fmin(wd, red_key[w]);
+        if (protect != H2O_PROTECT_RECENT && wd != wd) {     // the pattern covers every slot
+            wd = red_max[0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) wd = fmin(wd, red_max[w]);
+            key = key_all;
+            key_slot = key_all_slot;
+        }
         const unsigned long long win = (unsigned long long)__double_as_longlong(wd);
         const unsigned long long self_key =
             ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
-        const bool evict = wd == wd && (recent != 0 || win < self_key);
+        const bool evict = wd == wd && (protect != H2O_PROTECT_RECENT || recent != 0 || win < self_key);
         const bool mine = evict && key == win && key != NO_CANDIDATE;   // keys are unique (positions are)
         if (mine) lost_slot = key_slot;
         const unsigned long long b = __ballot(mine);
@@ -456,7 +475,7 @@ void decode_q4_kernel(
 #define H2O_DECODE_ARGS                                                                         \
     c.K, c.V, c.acc, c.pos, static_cast<const char *>(q), static_cast<const char *>(kn),        \
         static_cast<const char *>(vn), static_cast<char *>(out), c.k, (c.t < c.k ? c.t : c.k),  \
-        c.t, c.cfg.recent, c.scale, c.cfg.rank
+        c.t, c.cfg.recent, c.scale, c.cfg.rank, c.cfg.protect, c.cfg.stride
 
 template <int DT, int D, int NW, int U>
 hipError_t launch_q4(const h2o_cache &c, const void *q, const void *kn, const void *vn, void *out,

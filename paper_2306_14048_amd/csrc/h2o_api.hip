@@ -50,6 +50,10 @@ int check_config(const h2o_config *c)
     if ((int64_t)c->heavy + c->recent > H2O_MAX_BUDGET) return H2O_EUNSUPPORTED;
     if ((int64_t)c->batch * c->heads > (1 << 24)) return H2O_EUNSUPPORTED;
     if (c->kv_bits != 0 && c->kv_bits != 4) return H2O_EINVAL;
+    if (c->protect != H2O_PROTECT_RECENT && c->protect != H2O_PROTECT_STRIDED &&
+        c->protect != H2O_PROTECT_FIXED)
+        return H2O_EINVAL;
+    if (c->protect != H2O_PROTECT_RECENT && (c->stride < 1 || c->stride > (1 << 30))) return H2O_EINVAL;
     if (c->kv_bits == 4 && (int64_t)c->heavy + c->recent > H2O_Q4_MAX_BUDGET) return H2O_EUNSUPPORTED;
     return H2O_OK;
 }

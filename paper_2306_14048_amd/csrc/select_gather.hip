@@ -59,7 +59,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     const char *__restrict__ Kp, const char *__restrict__ Vp, const float *__restrict__ score,
     const float *__restrict__ base, const int32_t *__restrict__ pos_in, int n, int t_new,
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
-    int32_t *__restrict__ pos_g, int k, int heavy, int recent, int rank)
+    int32_t *__restrict__ pos_g, int k, int heavy, int recent, int rank, int protect, int stride)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     int *sel_l = reinterpret_cast<int *>(smem);        // [k] slot -> prompt position
@@ -88,10 +88,27 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
         __syncthreads();
         for (int s = tid; s < n; s += SG_NT) sel_l[s] = s;
     } else {
-        // candidates: the entries in front of the window of the last `recent`
-        // positions; positions ascend, so they are a prefix [0, older)
+        // Which entries compete.  With the recent window (protect 0) the candidates are
+        // the entries in front of the last `recent` positions; positions ascend, so they
+        // are a prefix [0, older) and `heavy` of them are kept.  With a sparse-attention
+        // pattern as the protected set, the entries the pattern covers for the last
+        // query (position t_new - 1) are kept and the best of the others fill the budget;
+        // should it cover more than the budget, the covered entries compete for all
+        // k slots and the others are dropped (the rule "evict one at a time, protection
+        // void once everything left is covered", in one shot).
         int older = n - recent;
-        if (pin) {
+        bool overflow = false;
+        int want = heavy;                              // candidates to keep
+        auto covered = [&](int j) { return is_protected(pos_of(j), t_new - 1, recent, protect, stride); };
+        if (protect != H2O_PROTECT_RECENT) {
+            int cnt = 0;
+            for (int j = tid; j < n; j += SG_NT) cnt += covered(j);
+            int total;
+            block_exclusive_scan(cnt, scan_l, total);
+            overflow = total > k;
+            want = overflow ? k : k - total;
+            __syncthreads();
+        } else if (pin) {
             int cnt = 0;
             for (int j = tid; j < n; j += SG_NT) cnt += pin[j] < t_new - recent;
             int total;
@@ -99,15 +116,24 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
             older = total;
             __syncthreads();
         }
+        auto is_cand = [&](int j) {
+            return protect == H2O_PROTECT_RECENT ? j < older : covered(j) == overflow;
+        };
+        auto always = [&](int j) {
+            return protect == H2O_PROTECT_RECENT ? j >= older : (!overflow && covered(j));
+        };
+        const int cand_end = protect == H2O_PROTECT_RECENT ? older : n;   // candidates lie in [0, cand_end)
         unsigned thr = 0, need = 0;                    // keep keys > thr, and `need` of those == thr
-        if (heavy > 0 && older > heavy) {
-            // radix select: the heavy-th largest key among the older tokens
+        if (want > 0) {
+            // radix select: the want-th largest key among the candidates (there are more
+            // than `want` of them: n exceeds the budget)
             unsigned prefix = 0, mask = 0;
-            need = (unsigned)heavy;
+            need = (unsigned)want;
             for (int shift = 24; shift >= 0; shift -= 8) {
                 for (int b = tid; b < 256; b += SG_NT) hist[b] = 0;
                 __syncthreads();
-                for (int j = tid; j < older; j += SG_NT) {
+                for (int j = tid; j < cand_end; j += SG_NT) {
+                    if (!is_cand(j)) continue;
                     const unsigned key = order_key(ranked(sc_of(j), j));
                     if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
                 }
@@ -136,38 +162,32 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
         const int per = (n + SG_NT - 1) / SG_NT;
         const int j0 = min(n, tid * per), j1 = min(n, j0 + per);
         int eq_cnt = 0;
-        if (heavy > 0)
-            for (int j = j0; j < min(j1, older); ++j) eq_cnt += order_key(ranked(sc_of(j), j)) == thr;
+        if (want > 0)
+            for (int j = j0; j < min(j1, cand_end); ++j)
+                eq_cnt += is_cand(j) && order_key(ranked(sc_of(j), j)) == thr;
         int eq_total;
         int eq_before = block_exclusive_scan(eq_cnt, scan_l, eq_total);
         // among equal scores the higher positions are kept: the last `need` of them
         const int eq_first_kept = eq_total - (int)need;
+        auto kept = [&](int j, int &e) {
+            if (always(j)) return true;
+            if (want <= 0 || !is_cand(j)) return false;
+            const unsigned key = order_key(ranked(sc_of(j), j));
+            if (key > thr) return true;
+            if (key == thr) { const bool keep = e >= eq_first_kept; ++e; return keep; }
+            return false;
+        };
         int keep_cnt = 0;
         {
             int e = eq_before;
-            for (int j = j0; j < j1; ++j) {
-                bool keep = j >= older;
-                if (!keep && heavy > 0) {
-                    const unsigned key = order_key(ranked(sc_of(j), j));
-                    if (key > thr) keep = true;
-                    else if (key == thr) { keep = e >= eq_first_kept; ++e; }
-                }
-                keep_cnt += keep;
-            }
+            for (int j = j0; j < j1; ++j) keep_cnt += kept(j, e);
         }
         int kept_total;
         int slot = block_exclusive_scan(keep_cnt, scan_l, kept_total);
         {
             int e = eq_before;
-            for (int j = j0; j < j1; ++j) {
-                bool keep = j >= older;
-                if (!keep && heavy > 0) {
-                    const unsigned key = order_key(ranked(sc_of(j), j));
-                    if (key > thr) keep = true;
-                    else if (key == thr) { keep = e >= eq_first_kept; ++e; }
-                }
-                if (keep) { if (slot < k) sel_l[slot] = j; ++slot; }
-            }
+            for (int j = j0; j < j1; ++j)
+                if (kept(j, e)) { if (slot < k) sel_l[slot] = j; ++slot; }
         }
     }
     __syncthreads();
@@ -283,7 +303,7 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
 #define H2O_SG(RB, QDT)                                                                         \
     hipLaunchKernelGGL((select_gather_kernel<RB, QDT>), dim3(heads), dim3(SG_NT), smem, st, Kp, \
                        Vp, score, base, pos_in, n, t_new, c.K, c.V, c.acc, c.pos, c.k,          \
-                       c.cfg.heavy, c.cfg.recent, c.cfg.rank)
+                       c.cfg.heavy, c.cfg.recent, c.cfg.rank, c.cfg.protect, c.cfg.stride)
     if (c.cfg.kv_bits == 4) {
         const int d = c.cfg.head_dim;
         switch (c.cfg.dtype) {

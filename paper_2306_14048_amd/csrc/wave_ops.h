@@ -136,6 +136,20 @@ __device__ inline float rank_value(float acc, int pos, int t, int rank)
     return rank == H2O_RANK_AVERAGED ? __fdiv_rn(acc, (float)(t - pos + 1)) : acc;
 }
 
+// What an eviction may not touch when the query sits at position t.  protect 0:
+// the last `recent` positions (the method's recent window).  Otherwise the
+// positions a sparse-attention pattern lets that query attend to (Sec. 5.2,
+// the strided and fixed patterns combined with heavy hitters): strided = a band
+// of `recent` positions and every stride-th position counted back from t;
+// fixed = the block of `stride` positions holding t and the last `recent`
+// positions of every block.
+__device__ inline bool is_protected(int p, int t, int recent, int protect, int stride)
+{
+    if (protect == H2O_PROTECT_STRIDED) return t - p < recent || (t - p) % stride == 0;
+    if (protect == H2O_PROTECT_FIXED) return p / stride == t / stride || p % stride >= stride - recent;
+    return p > t - recent;
+}
+
 // ---- 4-bit group-wise storage ------------------------------------------------------
 //
 // A lane holds 8 consecutive elements of a row (exact binary32 images); the 8

@@ -63,7 +63,12 @@ def test_size_queries_and_validation(hb):
         assert hb.h2o_cache_bytes(c) == 0
     assert hb.h2o_cache_bytes(hb.make_config(16, 32, 128, 205, 205, hb.H2O_F16, rank=hb.H2O_RANK_AVERAGED)) \
         == 2 * kv + 2 * meta
-    assert ctypes.sizeof(hb.h2o_config) == 36
+    assert ctypes.sizeof(hb.h2o_config) == 44
+    # the protected set: a pattern needs a period; unknown modes are refused
+    assert hb.h2o_cache_bytes(hb.make_config(1, 1, 128, 4, 4, hb.H2O_F16, protect=hb.H2O_PROTECT_STRIDED, stride=8)) > 0
+    assert hb.h2o_cache_bytes(hb.make_config(1, 1, 128, 4, 4, hb.H2O_F16, protect=hb.H2O_PROTECT_FIXED, stride=16)) > 0
+    assert hb.h2o_cache_bytes(hb.make_config(1, 1, 128, 4, 4, hb.H2O_F16, protect=hb.H2O_PROTECT_STRIDED, stride=0)) == 0
+    assert hb.h2o_cache_bytes(hb.make_config(1, 1, 128, 4, 4, hb.H2O_F16, protect=3, stride=8)) == 0
     # 4-bit storage: rows of head_dim/2 code bytes + 16 bytes of (scale, min) pairs
     q4 = hb.make_config(16, 32, 128, 205, 205, hb.H2O_F16, kv_bits=4)
     assert hb.h2o_cache_bytes(q4) == 2 * 16 * 32 * 410 * 80 + 2 * meta
