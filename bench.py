@@ -229,6 +229,8 @@ def main():
             cache._ws = None
             del Q, K, V
             caches.append(cache)
+            # (a line per layer: this set-up takes minutes and would otherwise be silent)
+            print("bench.py: layer %d of %d scored and compressed" % (layer + 1, L), file=sys.stderr, flush=True)
     for layer in range(L):
         steps_in.append(synth.make_steps(B, Hh, d, T, w.dtype, w.sigma, dev, layer=layer))
     outs = torch.empty((T, B, Hh, d), dtype=w.dtype, device=dev)
