@@ -253,15 +253,30 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
             const unsigned char *tbp = tile_l + tb * TILEB;
+            auto fragment = [&](int f, int mb) {
+                const int row = mb * 32 + l32;
+                return *reinterpret_cast<const uint4 *>(
+                    tbp + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
+            };
+            // the fragments of k-step f + 1 are requested before the MFMAs of k-step f
+            // are issued (the scheduling fences keep it that way; left alone the compiler
+            // requests a k-step's fragments and waits for them on the spot): an LDS read
+            // then has two MFMAs' time to come back
+            uint4 a_cur[MB], a_nxt[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) a_cur[mb] = fragment(0, mb);
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
+                if (f + 1 < NF) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const int row = mb * 32 + l32;
-                    const uint4 a = *reinterpret_cast<const uint4 *>(
-                        tbp + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
-                    acc[mb] = mma<DT>(a, st[f], acc[mb]);
+                    for (int mb = 0; mb < MB; ++mb) a_nxt[mb] = fragment(f + 1, mb);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) acc[mb] = mma<DT>(a_cur[mb], st[f], acc[mb]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) a_cur[mb] = a_nxt[mb];
             }
             __builtin_amdgcn_s_setprio(0);
         }
