@@ -350,7 +350,14 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
         tb = tb == NTB - 1 ? 0 : tb + 1;
         lb = (lb + 1) & (NLB - 1);
         dma_wait_upto<CPF>();
-        wg_barrier();
+        // The step's closing barrier takes the running sums as operands: pass 1's vector
+        // phase touches no memory, so only this data dependence keeps its arithmetic in
+        // front of the barrier.  (Left free, a build has put the whole vector phase behind
+        // it; the two wave groups then take turns instead of overlapping.)
+        if constexpr (COLSUM)
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : "+v"(c_run) : : "memory");
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : "+v"(m_run), "+v"(l_run) : : "memory");
     };
     // Tiles that need the mask: in pass 1 from the first key tile that reaches past
     // the position of this block's first query; in pass 2 up to the last query tile
