@@ -258,25 +258,34 @@ __global__ __launch_bounds__(NWV * 64, 4) void prefill_pass_kernel(
                 return *reinterpret_cast<const uint4 *>(
                     tbp + row * LROW + (((2 * f + half) ^ ((row >> RSH) & KMASK)) * 16));
             };
-            // the fragments of k-step f + 1 are requested before the MFMAs of k-step f
-            // are issued (the scheduling fences keep it that way; left alone the compiler
-            // requests a k-step's fragments and waits for them on the spot): an LDS read
-            // then has two MFMAs' time to come back
-            uint4 a_cur[MB], a_nxt[MB];
+            if constexpr (ROWB >= 256) {
+                // the fragments of k-step f + 1 are requested before the MFMAs of k-step f
+                // are issued (the scheduling fences keep it that way; left alone the compiler
+                // requests a k-step's fragments and waits for them on the spot): an LDS read
+                // then has two MFMAs' time to come back
+                uint4 a_cur[MB], a_nxt[MB];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) a_cur[mb] = fragment(0, mb);
+                for (int mb = 0; mb < MB; ++mb) a_cur[mb] = fragment(0, mb);
 #pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                if (f + 1 < NF) {
+                for (int f = 0; f < NF; ++f) {
+                    if (f + 1 < NF) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) a_nxt[mb] = fragment(f + 1, mb);
+                        for (int mb = 0; mb < MB; ++mb) a_nxt[mb] = fragment(f + 1, mb);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) acc[mb] = mma<DT>(a_cur[mb], st[f], acc[mb]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) a_cur[mb] = a_nxt[mb];
                 }
-                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                // (128-byte rows: four k-steps per tile; the read-ahead's eight registers
+                // would cost pass 2 its third workgroup per CU, which is worth more)
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) acc[mb] = mma<DT>(a_cur[mb], st[f], acc[mb]);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int f = 0; f < NF; ++f)
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) a_cur[mb] = a_nxt[mb];
+                    for (int mb = 0; mb < MB; ++mb) acc[mb] = mma<DT>(fragment(f, mb), st[f], acc[mb]);
             }
             __builtin_amdgcn_s_setprio(0);
         }
