@@ -71,7 +71,9 @@ __host__ __device__ constexpr int code_bit(int j) { return j < 5 ? 4 * j : 4 * (
 // (three per CU); deeper rings run at two waves per SIMD.  Eight waves per head
 // with half the rounds each were measured slower (more waves redo the softmax and
 // bookkeeping than the shorter rounds save).
-template <int DT, int D, int NW, int U>
+// PAT: built for a sparse-attention pattern as the protected set (the plain recent
+// window's build carries none of that code).
+template <int DT, int D, int NW, int U, bool PAT>
 __global__ __launch_bounds__(NW * 64, U * (64 / (D / 32)) == 64 ? 4 : (NW == 4 && U * (64 / (D / 32)) == 128) ? 3 : 2)
 void decode_q4_kernel(
     char *__restrict__ Kc, char *__restrict__ Vc, float *__restrict__ acc_g,
@@ -402,18 +404,17 @@ void decode_q4_kernel(
             const unsigned long long c =
                 ((unsigned long long)__float_as_uint(rank_value(acc_j[s], pos_j[s], t, rank)) << 32) |
                 (unsigned)pos_j[s];
-            if (protect == H2O_PROTECT_RECENT ? pos_j[s] <= t - recent
-                                              : !is_protected(pos_j[s], t, recent, protect, stride)) {
+            if (PAT ? !is_protected(pos_j[s], t, recent, protect, stride) : pos_j[s] <= t - recent) {
                 if (c < key) { key = c; key_slot = my_slot[s]; }
             }
-            if (protect != H2O_PROTECT_RECENT && c < key_all) { key_all = c; key_all_slot = my_slot[s]; }
+            if (PAT && c < key_all) { key_all = c; key_all_slot = my_slot[s]; }
         }
     }
     {
         const double kw = wave_min_f64(__longlong_as_double((long long)key));
         if (lane == 0) red_key[wave] = kw;
     }
-    if (protect != H2O_PROTECT_RECENT) {
+    if constexpr (PAT) {
         const double ka = wave_min_f64(__longlong_as_double((long long)key_all));
         if (lane == 0) red_max[wave] = ka;
     }
@@ -439,7 +440,7 @@ void decode_q4_kernel(
         double wd = red_key[0];
 #pragma unroll
         for (int w = 1; w < NW; ++w) wd = fmin(wd, red_key[w]);
-        if (protect != H2O_PROTECT_RECENT && wd != wd) {     // the pattern covers every slot
+        if (PAT && wd != wd) {                               // the pattern covers every slot
             wd = red_max[0];
 #pragma unroll
             for (int w = 1; w < NW; ++w) wd = fmin(wd, red_max[w]);
@@ -449,7 +450,7 @@ void decode_q4_kernel(
         const unsigned long long win = (unsigned long long)__double_as_longlong(wd);
         const unsigned long long self_key =
             ((unsigned long long)__float_as_uint(p_self) << 32) | (unsigned)t;
-        const bool evict = wd == wd && (protect != H2O_PROTECT_RECENT || recent != 0 || win < self_key);
+        const bool evict = wd == wd && (PAT || recent != 0 || win < self_key);
         const bool mine = evict && key == win && key != NO_CANDIDATE;   // keys are unique (positions are)
         if (mine) lost_slot = key_slot;
         const unsigned long long b = __ballot(mine);
@@ -485,18 +486,19 @@ hipError_t launch_q4(const h2o_cache &c, const void *q, const void *kn, const vo
     constexpr size_t smem = (size_t)NW * OWN * 8 + (size_t)NW * 24 + (size_t)LPR * 34 * 8 +
                             (size_t)NW * OWN * 4 + (size_t)NW * 16 + 384 +
                             (size_t)NW * RPW * (D + 4) * 4 + 16;
-    auto kern = decode_q4_kernel<DT, D, NW, U>;
-    if (smem > 48 * 1024) {
-        static bool raised = false;
-        if (!raised) {
+    auto launch = [&](auto kern, bool &raised) -> hipError_t {
+        if (smem > 48 * 1024 && !raised) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
             if (e != hipSuccess) return e;
             raised = true;
         }
-    }
-    hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st, H2O_DECODE_ARGS);
-    return hipGetLastError();
+        hipLaunchKernelGGL(kern, dim3(c.cfg.batch * c.cfg.heads), dim3(NW * 64), smem, st, H2O_DECODE_ARGS);
+        return hipGetLastError();
+    };
+    static bool raised_window = false, raised_pattern = false;
+    if (c.cfg.protect == H2O_PROTECT_RECENT) return launch(decode_q4_kernel<DT, D, NW, U, false>, raised_window);
+    return launch(decode_q4_kernel<DT, D, NW, U, true>, raised_pattern);
 }
 
 // Rounds per wave follow the number of occupied slots (capacity NW * U * RPW).
