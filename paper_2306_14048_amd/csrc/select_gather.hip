@@ -53,8 +53,9 @@ __device__ inline int block_exclusive_scan(int v, int *scratch, int &total)
 // score[j]); t_new = number of tokens seen once these are stored.
 // QDT < 0: the cache stores rows as they are (ROWB bytes each).  QDT = an element
 // type: the cache stores 4-bit codes and the kept rows (ROWB bytes of QDT
-// elements) are quantised on their way in.
-template <int ROWB, int QDT>
+// elements) are quantised on their way in.  PAT: built for a sparse-attention
+// pattern as the protected set (the recent-window build carries none of that code).
+template <int ROWB, int QDT, bool PAT>
 __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
     const char *__restrict__ Kp, const char *__restrict__ Vp, const float *__restrict__ score,
     const float *__restrict__ base, const int32_t *__restrict__ pos_in, int n, int t_new,
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
         bool overflow = false;
         int want = heavy;                              // candidates to keep
         auto covered = [&](int j) { return is_protected(pos_of(j), t_new - 1, recent, protect, stride); };
-        if (protect != H2O_PROTECT_RECENT) {
+        if constexpr (PAT) {
             int cnt = 0;
             for (int j = tid; j < n; j += SG_NT) cnt += covered(j);
             int total;
@@ -117,12 +118,14 @@ __global__ __launch_bounds__(SG_NT) void select_gather_kernel(
             __syncthreads();
         }
         auto is_cand = [&](int j) {
-            return protect == H2O_PROTECT_RECENT ? j < older : covered(j) == overflow;
+            if constexpr (PAT) return covered(j) == overflow;
+            else return j < older;
         };
         auto always = [&](int j) {
-            return protect == H2O_PROTECT_RECENT ? j >= older : (!overflow && covered(j));
+            if constexpr (PAT) return !overflow && covered(j);
+            else return j >= older;
         };
-        const int cand_end = protect == H2O_PROTECT_RECENT ? older : n;   // candidates lie in [0, cand_end)
+        const int cand_end = PAT ? n : older;          // candidates lie in [0, cand_end)
         unsigned thr = 0, need = 0;                    // keep keys > thr, and `need` of those == thr
         if (want > 0) {
             // radix select: the want-th largest key among the candidates (there are more
@@ -300,10 +303,16 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
     const int rowb = c.cfg.head_dim * c.esize;
     const size_t smem = (size_t)c.k * sizeof(int);
     const char *Kp = static_cast<const char *>(K), *Vp = static_cast<const char *>(V);
+#define H2O_SG_ARGS                                                                             \
+    dim3(heads), dim3(SG_NT), smem, st, Kp, Vp, score, base, pos_in, n, t_new, c.K, c.V, c.acc,     \
+        c.pos, c.k, c.cfg.heavy, c.cfg.recent, c.cfg.rank, c.cfg.protect, c.cfg.stride
 #define H2O_SG(RB, QDT)                                                                         \
-    hipLaunchKernelGGL((select_gather_kernel<RB, QDT>), dim3(heads), dim3(SG_NT), smem, st, Kp, \
-                       Vp, score, base, pos_in, n, t_new, c.K, c.V, c.acc, c.pos, c.k,          \
-                       c.cfg.heavy, c.cfg.recent, c.cfg.rank, c.cfg.protect, c.cfg.stride)
+    do {                                                                                        \
+        if (c.cfg.protect == H2O_PROTECT_RECENT)                                                \
+            hipLaunchKernelGGL((select_gather_kernel<RB, QDT, false>), H2O_SG_ARGS);            \
+        else                                                                                    \
+            hipLaunchKernelGGL((select_gather_kernel<RB, QDT, true>), H2O_SG_ARGS);             \
+    } while (0)
     if (c.cfg.kv_bits == 4) {
         const int d = c.cfg.head_dim;
         switch (c.cfg.dtype) {
@@ -320,6 +329,7 @@ hipError_t h2o_launch_select_gather(const h2o_cache &c, const void *K, const voi
     default: return hipErrorInvalidValue;
     }
 #undef H2O_SG
+#undef H2O_SG_ARGS
     return hipGetLastError();
 }
 
